@@ -1,0 +1,197 @@
+/*
+ * es_oracle.c -- plain CPU oracle for edge-sampled SpMM.  TEST INFRASTRUCTURE
+ * ONLY: nothing on the product path (the HIP library, its Python binding) may
+ * link, load or call this file; only the test-suite, the smoke check and the
+ * benchmark's cpu_baseline leg do.  It shares no code, header, table or
+ * constant generator with the HIP path.
+ *
+ * What it computes (paper: Algorithm 1 "CacheSample"; Section 4.2 cache-first
+ * edge sampling; Section 4.4 sampling strategies, Equation 2):
+ *
+ *   for every row r of the CSR matrix A (n = number of stored entries):
+ *       k = min(n, W)                       -- Alg. 1 "S = min(row_nnz, width)"
+ *       for slot i = 0 .. k-1:
+ *           idx_i  = sample index of slot i -- Bucket / FastRand rule
+ *           kept_i = rowptr[r] + idx_i      -- a position in colidx / vals
+ *       Y[r, c] = sum_i vals[kept_i] * X[colidx[kept_i], c]   (fp64)
+ *
+ *   mode FULL is the plain definition Y = A * X (every entry, in order).
+ *
+ * Readings of the paper taken here (each is a documented decision):
+ *   - Section 4.2 says a row with n <= W is fetched whole, while Alg. 1 routes
+ *     every slot through the sample-index function; FastRand's hash would
+ *     collapse such a row when 577 divides n.  Reading: n <= W => idx_i = i in
+ *     every mode.
+ *   - Equation 2, idx = (i * 577) mod n, repeats positions when 577 | n.  The
+ *     sampler must keep k DISTINCT entries, so the multiplier is the first of
+ *     the primes 577, 587, 593, 599 that does not divide n (their product
+ *     exceeds 2^31, so one always qualifies).  Whenever 577 does not divide n
+ *     this is Equation 2 exactly as printed.
+ *   - The paper's sampler is static (Section 6.2).  A non-zero seed adds a
+ *     per-row rotation: idx = (off + i*P) mod n with off = (high 32 bits of
+ *     the (r+1)-th output of the SplitMix64 generator seeded with `seed`)
+ *     mod n.  seed == 0 => off = 0 => Equation 2.  Bucket ignores the seed.
+ *   - Parity status of the rotation: SplitMix64 itself is pinned by its
+ *     published test vectors; the rotation is this build's addition, so there
+ *     is nothing in the paper to pin it against (it is pinned only by its
+ *     written definition above and the distinctness / subset invariants).
+ *
+ * Sums are accumulated in double, slot by slot in slot order.  `denom` is
+ * sum_i |vals[kept_i]| * |X[colidx[kept_i], c]|, the scale of the parity bound.
+ *
+ * Rows are independent, so the row loop carries an OpenMP "parallel for";
+ * that is the only concession to speed.
+ */
+#include <stddef.h>
+#include <stdint.h>
+#include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_FULL = 0, ORACLE_BUCKET = 1, ORACLE_FASTRAND = 2 };
+
+/* One output of SplitMix64: the state is advanced by the golden-ratio
+ * increment, then mixed (Steele, Lea, Flood 2014; Vigna's public-domain
+ * reference).  *state is updated. */
+uint64_t es_oracle_splitmix64_next(uint64_t *state)
+{
+    uint64_t z = (*state += UINT64_C(0x9E3779B97F4A7C15));
+    z = (z ^ (z >> 30)) * UINT64_C(0xBF58476D1CE4E5B9);
+    z = (z ^ (z >> 27)) * UINT64_C(0x94D049BB133111EB);
+    return z ^ (z >> 31);
+}
+
+/* (r+1)-th output of SplitMix64(seed), computed by stepping the generator. */
+static uint64_t splitmix64_nth(uint64_t seed, uint64_t count)
+{
+    /* stepping r+1 times is O(r); the state after `count` steps is
+     * seed + count*increment (mod 2^64), so jump there and take one step back */
+    uint64_t state = seed + (count - 1) * UINT64_C(0x9E3779B97F4A7C15);
+    return es_oracle_splitmix64_next(&state);
+}
+
+/* FastRand multiplier for a row of n entries (n >= 1). */
+uint32_t es_oracle_multiplier(int64_t n)
+{
+    static const uint32_t primes[4] = { 577u, 587u, 593u, 599u };
+    for (int t = 0; t < 4; ++t)
+        if (n % (int64_t)primes[t] != 0) return primes[t];
+    return 0; /* unreachable for n < 577*587*593*599 */
+}
+
+/* Row rotation for FastRand. */
+uint64_t es_oracle_offset(uint64_t seed, int64_t row, int64_t n)
+{
+    if (seed == 0) return 0;
+    uint64_t out = splitmix64_nth(seed, (uint64_t)row + 1u);
+    return (out >> 32) % (uint64_t)n;
+}
+
+/* Number of entries row keeps. */
+int64_t es_oracle_kept_count(int32_t mode, int64_t n, int64_t W)
+{
+    if (mode == ORACLE_FULL) return n;
+    return n < W ? n : W;
+}
+
+/* Position inside the row (0 .. n-1) that slot i reads. */
+int64_t es_oracle_sample_index(int32_t mode, uint64_t seed, int64_t row,
+                               int64_t i, int64_t n, int64_t W)
+{
+    if (mode == ORACLE_FULL || mode == ORACLE_BUCKET || n <= W) return i;
+    uint64_t P = es_oracle_multiplier(n);
+    uint64_t off = es_oracle_offset(seed, row, n);
+    return (int64_t)((off + (uint64_t)i * P) % (uint64_t)n);
+}
+
+static int bad_mode(int32_t mode)
+{
+    return mode != ORACLE_FULL && mode != ORACLE_BUCKET && mode != ORACLE_FASTRAND;
+}
+
+/*
+ * Kept CSR positions, ordered by slot, for the rows listed in `rows`
+ * (rows == NULL: rows 0 .. nrows-1).  pos is [nrows x stride]; slots at or
+ * beyond the row's count are set to -1.  cnt[j] is the row's kept count
+ * (which may exceed stride; only the first `stride` slots are written then).
+ * Returns 0, or -1 on a bad argument.
+ */
+int es_oracle_kept(const int32_t *rowptr, int64_t N, int64_t W, int32_t mode,
+                   uint64_t seed, const int64_t *rows, int64_t nrows,
+                   int32_t *pos, int64_t stride, int32_t *cnt)
+{
+    if (!rowptr || !pos || !cnt || N < 0 || nrows < 0 || stride < 0 || bad_mode(mode))
+        return -1;
+    if (mode != ORACLE_FULL && W < 1) return -1;
+    for (int64_t j = 0; j < nrows; ++j) {
+        int64_t r = rows ? rows[j] : j;
+        if (r < 0 || r >= N) return -1;
+        int64_t base = rowptr[r];
+        int64_t n = (int64_t)rowptr[r + 1] - base;
+        int64_t k = es_oracle_kept_count(mode, n, W);
+        cnt[j] = (int32_t)k;
+        for (int64_t i = 0; i < stride; ++i) {
+            if (i < k)
+                pos[j * stride + i] =
+                    (int32_t)(base + es_oracle_sample_index(mode, seed, r, i, n, W));
+            else
+                pos[j * stride + i] = -1;
+        }
+    }
+    return 0;
+}
+
+/*
+ * Yref[j, c] and denom[j, c] (both [nrows x F], double) for the listed rows
+ * (rows == NULL: rows 0 .. nrows-1).  vals == NULL means every stored entry
+ * is 1 (unweighted graph, Section 2.2).  denom may be NULL.
+ * Returns 0, or -1 on a bad argument.
+ */
+int es_oracle_spmm(const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                   const float *X, int64_t ldx, int64_t N, int64_t F, int64_t W,
+                   int32_t mode, uint64_t seed, const int64_t *rows, int64_t nrows,
+                   double *Yref, double *denom)
+{
+    if (!rowptr || !X || !Yref || N < 0 || F < 1 || ldx < F || nrows < 0 || bad_mode(mode))
+        return -1;
+    if (mode != ORACLE_FULL && W < 1) return -1;
+    if (!colidx && N > 0 && rowptr[N] > 0) return -1;
+    if (rows)
+        for (int64_t j = 0; j < nrows; ++j)
+            if (rows[j] < 0 || rows[j] >= N) return -1;
+    if (!rows && nrows > N) return -1;
+
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t j = 0; j < nrows; ++j) {
+        int64_t r = rows ? rows[j] : j;
+        int64_t base = rowptr[r];
+        int64_t n = (int64_t)rowptr[r + 1] - base;
+        int64_t k = es_oracle_kept_count(mode, n, W);
+        double *y = Yref + j * F;
+        double *d = denom ? denom + j * F : NULL;
+        for (int64_t c = 0; c < F; ++c) y[c] = 0.0;
+        if (d) for (int64_t c = 0; c < F; ++c) d[c] = 0.0;
+        for (int64_t i = 0; i < k; ++i) {
+            int64_t p = base + es_oracle_sample_index(mode, seed, r, i, n, W);
+            double a = vals ? (double)vals[p] : 1.0;
+            const float *x = X + (int64_t)colidx[p] * ldx;
+            for (int64_t c = 0; c < F; ++c) y[c] += a * (double)x[c];
+            if (d) {
+                double aa = fabs(a);
+                for (int64_t c = 0; c < F; ++c) d[c] += aa * fabs((double)x[c]);
+            }
+        }
+    }
+    return 0;
+}
+
+/* Threads the row loop of es_oracle_spmm uses. */
+int es_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
