@@ -1,0 +1,119 @@
+/*
+ * es_spmm.h -- C ABI of the MI355X (gfx950) edge-sampled SpMM library.
+ *
+ * The library computes the GNN feature aggregation  Y = sample_W(A) * X  of the
+ * ES-SpMM / "CacheSample" method (paper: Section 4, Algorithm 1): A is an N x N
+ * sparse matrix in plain 3-array CSR (Section 2.2), X and Y are dense row-major
+ * fp32 (Section 4.1); every row of A is capped at W stored entries by an
+ * in-kernel sampler (Section 4.2, "cache-first edge sampling") whose picks are
+ * staged in on-chip memory (LDS) and then multiplied with the gathered rows of
+ * X (Section 4.3).
+ *
+ * Conventions for every entry point
+ *   - All array pointers are DEVICE pointers on the current HIP device, owned by
+ *     the caller; the library neither allocates, frees nor retains them.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream).  Calls return as soon as the launch is queued; they never
+ *     synchronise and never read device memory on the host.
+ *   - Return value: ES_OK or a negative es_status_t.  Nothing aborts or throws.
+ *     On any error no kernel is launched and no output is touched.
+ *   - Not checked (caller's contract): rowptr[0] == 0, rowptr non-decreasing,
+ *     rowptr[N] == nnz < 2^31, 0 <= colidx[p] < N, X and Y do not overlap.
+ */
+#ifndef ES_SPMM_H
+#define ES_SPMM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Sampling strategy (Section 4.4).  FULL keeps every entry: the exact product. */
+typedef enum { ES_FULL = 0, ES_BUCKET = 1, ES_FASTRAND = 2 } es_mode_t;
+
+typedef enum {
+    ES_OK = 0,
+    ES_ERR_INVALID_ARG = -1,  /* null pointer, negative size, ld < F, W < 1, bad mode */
+    ES_ERR_UNSUPPORTED = -2,  /* shape outside what the kernels cover               */
+    ES_ERR_LAUNCH = -3        /* the HIP runtime rejected the launch                */
+} es_status_t;
+
+/*
+ * es_spmm -- Algorithm 1 of the paper, fused sampling + SpMM.
+ *
+ * For every row r (n = rowptr[r+1] - rowptr[r] stored entries):
+ *     k = n                      for ES_FULL
+ *     k = min(n, W)              for ES_BUCKET / ES_FASTRAND   (Section 4.2)
+ *     slot i in [0, k) reads the row's entry number
+ *         i                               ES_FULL, ES_BUCKET, or n <= W
+ *                                         (Section 4.2: a row that fits is kept
+ *                                         whole; Section 4.4: Bucket = first W)
+ *         (off + i * P) mod n             ES_FASTRAND with n > W  (Equation 2)
+ *       P   = first of 577, 587, 593, 599 that does not divide n (577 is the
+ *             paper's multiplier; the fallbacks keep the k picks distinct)
+ *       off = 0 when seed == 0 (exactly Equation 2); otherwise the high 32 bits
+ *             of output number r+1 of the SplitMix64 generator seeded with
+ *             `seed`, reduced mod n (a per-row rotation; the picks stay distinct)
+ *     Y[r, c] = sum over the k slots of vals[p] * X[colidx[p], c],  c in [0, F)
+ * Y is overwritten (rows with n == 0 become zeros).  Accumulation is fp32; the
+ * summation order is unspecified.
+ *
+ *   rowptr  [N+1] int32          colidx [nnz] int32
+ *   vals    [nnz] fp32, or NULL = every stored entry is 1 (unweighted graph)
+ *   X       N rows of F fp32, row stride ldx >= F elements
+ *   Y       N rows of F fp32, row stride ldy >= F elements
+ *   nnz     rowptr[N]; used only to pick a launch shape (mean row length) --
+ *           results never depend on it
+ *   W       cap per row, >= 1 (ignored for ES_FULL).  Any W is accepted: rows
+ *           longer than one LDS tile are staged tile by tile.
+ *   seed    see above; ES_BUCKET and ES_FULL ignore it
+ * 128-bit accesses are used when F, ldx, ldy are multiples of 4 and X, Y are
+ * 16-byte aligned; any other shape takes the 32-bit kernels.
+ */
+int es_spmm(const int32_t* rowptr, const int32_t* colidx, const float* vals,
+            const float* X, float* Y,
+            int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy,
+            int32_t W, int32_t mode, uint64_t seed, void* stream);
+
+/*
+ * es_spmm_sample_edges -- the sampler of Section 4.2 / 4.4 on its own, for
+ * verification.  Runs the same device sampler and slot-to-lane schedule as
+ * es_spmm and writes, for row r and slot i < k_r, the CSR position
+ * rowptr[r] + (entry number of slot i) into pos[r * W + i]; slots i >= k_r get
+ * -1; cnt[r] = k_r = min(n_r, W).  mode must be ES_BUCKET or ES_FASTRAND.
+ *   pos [N * W] int32 (device), cnt [N] int32 (device); N * W must be < 2^31.
+ *   rows_per_wave: 0 = the library's default schedule, else a power of two in
+ *   [1, 64] forcing how many rows share a wavefront (every value must produce
+ *   the same output; tests sweep it).
+ */
+int es_spmm_sample_edges(const int32_t* rowptr, int64_t N, int32_t W, int32_t mode,
+                         uint64_t seed, int32_t rows_per_wave,
+                         int32_t* pos, int32_t* cnt, void* stream);
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* es_spmm_status_string(int status);
+
+/* Largest W es_spmm accepts for feature width F (tiles are refilled, so this is
+ * INT32_MAX for every valid F; 0 for F < 1). */
+int32_t es_spmm_max_W(int32_t F);
+
+/* Number of (colidx, vals) slots one row can hold in LDS at once when
+ * `rows_per_wave` rows share a wavefront (Section 4.2's shared-memory width);
+ * rows_per_wave = 0 reports the single-row tile.  0 for an invalid argument. */
+int32_t es_spmm_tile_slots(int32_t rows_per_wave);
+
+/*
+ * Launch-shape override for es_spmm: how many rows share one wavefront
+ * (Section 4.2 assigns a thread group per row; here the group size is
+ * 64 / rows_per_wave lanes).  0 restores the built-in choice; otherwise a power
+ * of two in [1, 64], lowered when F needs more lanes per row.  Process-wide and
+ * not thread-safe; meant for tuning sweeps and tests.  Every value yields the
+ * same sampled edges; Y differs only by fp32 summation order.
+ */
+int es_spmm_set_rows_per_wave(int32_t rows_per_wave);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ES_SPMM_H */

@@ -1,0 +1,21 @@
+"""MI355X-native edge-sampled SpMM (ES-SpMM).
+
+Thin binding over the C-ABI library ``libes_spmm.so`` (see ``include/es_spmm.h``):
+argument marshalling only -- every step of the computation runs in the HIP
+kernels.  PyTorch supplies device memory and streams.
+"""
+from .binding import (  # noqa: F401
+    ES_BUCKET,
+    ES_FASTRAND,
+    ES_FULL,
+    MODES,
+    EsSpmmError,
+    es_spmm,
+    es_spmm_max_W,
+    es_spmm_sample_edges,
+    es_spmm_set_rows_per_wave,
+    es_spmm_status_string,
+    es_spmm_tile_slots,
+    library_path,
+    load_library,
+)

@@ -1,0 +1,148 @@
+"""ctypes binding of libes_spmm.so: same names as the C ABI, tensors in, status
+checked.  No arithmetic happens here."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+ES_FULL, ES_BUCKET, ES_FASTRAND = 0, 1, 2
+MODES = {"full": ES_FULL, "bucket": ES_BUCKET, "fastrand": ES_FASTRAND}
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libes_spmm.so")
+_lib = None
+
+
+class EsSpmmError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {es_spmm_status_string(status)} ({status})")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the HIP library; raises if it has not been built (there is no
+    fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2104_10716_amd.build` "
+            "(or __graft_entry__.build()); there is no CPU fallback")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp = ctypes.c_void_p
+    lib.es_spmm.restype = ctypes.c_int
+    lib.es_spmm.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                            ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                            ctypes.c_uint64, vp]
+    lib.es_spmm_sample_edges.restype = ctypes.c_int
+    lib.es_spmm_sample_edges.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                         ctypes.c_uint64, ctypes.c_int32, vp, vp, vp]
+    lib.es_spmm_status_string.restype = ctypes.c_char_p
+    lib.es_spmm_status_string.argtypes = [ctypes.c_int]
+    lib.es_spmm_max_W.restype = ctypes.c_int32
+    lib.es_spmm_max_W.argtypes = [ctypes.c_int32]
+    lib.es_spmm_tile_slots.restype = ctypes.c_int32
+    lib.es_spmm_tile_slots.argtypes = [ctypes.c_int32]
+    lib.es_spmm_set_rows_per_wave.restype = ctypes.c_int
+    lib.es_spmm_set_rows_per_wave.argtypes = [ctypes.c_int32]
+    _lib = lib
+    return lib
+
+
+def _mode(mode) -> int:
+    return MODES[mode] if isinstance(mode, str) else int(mode)
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _dev_ptr(t, dtype, name):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr() or None
+
+
+def es_spmm_status_string(status: int) -> str:
+    return load_library().es_spmm_status_string(int(status)).decode()
+
+
+def es_spmm_max_W(F: int) -> int:
+    return int(load_library().es_spmm_max_W(int(F)))
+
+
+def es_spmm_tile_slots(rows_per_wave: int = 0) -> int:
+    return int(load_library().es_spmm_tile_slots(int(rows_per_wave)))
+
+
+def es_spmm_set_rows_per_wave(rows_per_wave: int) -> None:
+    rc = load_library().es_spmm_set_rows_per_wave(int(rows_per_wave))
+    if rc != 0:
+        raise EsSpmmError(rc, "es_spmm_set_rows_per_wave")
+
+
+def es_spmm(rowptr, colidx, vals, X, Y, W: int, mode, seed: int = 0, F: Optional[int] = None,
+            stream=None):
+    """Y[:, :F] = sample_W(A) @ X[:, :F] on the tensors' device; returns Y.
+    rowptr/colidx int32, vals float32 or None, X/Y 2-D float32 with unit column
+    stride (row stride = leading dimension).  Enqueued on `stream` (default:
+    torch's current stream); not synchronised."""
+    import torch
+    lib = load_library()
+    if X.dim() != 2 or Y.dim() != 2 or X.stride(1) != 1 or Y.stride(1) != 1:
+        raise ValueError("X and Y must be 2-D with contiguous columns")
+    N = rowptr.numel() - 1
+    if X.shape[0] != N or Y.shape[0] != N:
+        raise ValueError("X and Y need one row per CSR row")
+    if F is None:
+        F = X.shape[1]
+    if F > X.shape[1] or F > Y.shape[1]:
+        raise ValueError("F exceeds the width of X or Y")
+    ldx = X.stride(0) if N > 1 else max(X.shape[1], 1)
+    ldy = Y.stride(0) if N > 1 else max(Y.shape[1], 1)
+    nnz = colidx.numel()
+    if vals is not None and vals.numel() != nnz:
+        raise ValueError("vals and colidx differ in length")
+    rc = lib.es_spmm(_dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(colidx, torch.int32, "colidx"),
+                     _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(X, torch.float32, "X"),
+                     _dev_ptr(Y, torch.float32, "Y"), N, nnz, int(F), int(ldx), int(ldy),
+                     int(W), _mode(mode), int(seed) & 0xFFFFFFFFFFFFFFFF, _stream_ptr(stream))
+    if rc != 0:
+        raise EsSpmmError(rc, "es_spmm")
+    return Y
+
+
+def es_spmm_sample_edges(rowptr, W: int, mode, seed: int = 0, rows_per_wave: int = 0,
+                         pos=None, cnt=None, stream=None):
+    """(pos [N, W] int32, cnt [N] int32) on the device of rowptr."""
+    import torch
+    lib = load_library()
+    N = rowptr.numel() - 1
+    if pos is None:
+        pos = torch.empty((N, int(W)), dtype=torch.int32, device=rowptr.device)
+    if cnt is None:
+        cnt = torch.empty((N,), dtype=torch.int32, device=rowptr.device)
+    if pos.numel() != N * int(W) or cnt.numel() != N or not pos.is_contiguous():
+        raise ValueError("pos must be a contiguous [N, W] tensor and cnt [N]")
+    rc = lib.es_spmm_sample_edges(_dev_ptr(rowptr, torch.int32, "rowptr"), N, int(W), _mode(mode),
+                                  int(seed) & 0xFFFFFFFFFFFFFFFF, int(rows_per_wave),
+                                  _dev_ptr(pos, torch.int32, "pos"), _dev_ptr(cnt, torch.int32, "cnt"),
+                                  _stream_ptr(stream))
+    if rc != 0:
+        raise EsSpmmError(rc, "es_spmm_sample_edges")
+    return pos, cnt

@@ -1,0 +1,478 @@
+// es_spmm.hip -- edge-sampled SpMM for gfx950 (MI355X), C ABI in include/es_spmm.h.
+//
+// Paper: Algorithm 1 ("CacheSample"): stage 1 samples at most W entries of each
+// CSR row into on-chip memory (Section 4.2, sampling rules of Section 4.4 /
+// Equation 2), stage 2 multiplies the staged entries with gathered rows of the
+// dense matrix (Section 4.3).
+//
+// Mapping to CDNA4 (differs from the paper's 512-thread CUDA blocks on purpose):
+//   * A wavefront (64 lanes) owns R = 2^logR consecutive rows.  The 64/R lanes of
+//     a row ("team") are E x G: G lanes span the feature columns with VEC-wide
+//     loads (CH column chunks per lane), E edge slots run side by side and are
+//     summed with cross-lane shuffles at the end.
+//   * Each wave has a private LDS tile of kTileSlots (column, value) pairs,
+//     T = kTileSlots/R per row.  Stage 1: the team's lanes evaluate the sampler
+//     for slots t, t+64/R, ... and copy (colidx, vals) into the tile.  Stage 2:
+//     lanes read a slot as one 64-bit LDS broadcast and issue U independent
+//     VEC-wide global loads of X before the first FMA.  Rows longer than a tile
+//     (full mode, or W > T) refill the tile; no barrier other than wave-level
+//     ordering is needed because a tile is private to its wave.
+//   * Workgroup ids are remapped so each of the 8 XCDs (one L2 each) walks one
+//     contiguous range of rows.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "es_spmm.h"
+
+namespace {
+
+constexpr int kWaveSize = 64;
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlockThreads = kWaveSize * kWavesPerBlock;
+constexpr int kTileSlots = 512;                       // (col, val) slots per wave
+constexpr int kWaveTileStride = kTileSlots + 64;      // + one pad slot per row slot
+constexpr int kNumXcd = 8;
+
+struct Args {
+    const int32_t* rowptr;
+    const int32_t* colidx;
+    const float* vals;
+    const float* X;
+    float* Y;
+    int64_t N;
+    uint64_t seed;
+    int32_t F, ldx, ldy, W, mode, logR;
+    uint32_t nblocks;          // workgroups that carry rows
+    uint32_t blocks_per_xcd;   // ceil(nblocks / 8)
+};
+
+// ---------------------------------------------------------------------------
+// Sampler (Section 4.4).  One instance per lane walks the slots
+// first, first + stride, first + 2*stride, ... of one row and returns the entry
+// number inside the row for each.  Bucket / full / short rows: the slot number
+// itself.  FastRand on a long row: (off + slot * P) mod n, kept incrementally
+// (one add and one conditional subtract per slot instead of a modulo).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t splitmix64_output(uint64_t seed, uint64_t count)
+{
+    // `count`-th output (1-based) of SplitMix64 seeded with `seed`
+    uint64_t z = seed + count * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+struct RowSampler {
+    uint32_t idx;    // entry number the next call returns
+    uint32_t step;   // increment per call, already reduced mod n
+    uint32_t wrap;   // n for FastRand, 0xFFFFFFFF when no wrap can happen
+
+    // requires first < 65536 and stride <= 64
+    __device__ __forceinline__ void init(int mode, uint64_t seed, int64_t row, uint32_t n,
+                                         uint32_t W, uint32_t first, uint32_t stride)
+    {
+        if (mode != ES_FASTRAND || n <= W) {
+            idx = first;
+            step = stride;
+            wrap = 0xFFFFFFFFu;
+            return;
+        }
+        const uint32_t P = (n % 577u) ? 577u : (n % 587u) ? 587u : (n % 593u) ? 593u : 599u;
+        uint32_t off = 0;
+        if (seed != 0)
+            off = (uint32_t)(splitmix64_output(seed, (uint64_t)row + 1u) >> 32) % n;
+        idx = (uint32_t)(((uint64_t)off + (uint64_t)first * P) % n);
+        step = (stride * P) % n;
+        wrap = n;
+    }
+
+    __device__ __forceinline__ uint32_t next()
+    {
+        const uint32_t cur = idx;
+        uint32_t nx = idx + step;          // < 2n < 2^32
+        if (nx >= wrap) nx -= wrap;
+        idx = nx;
+        return cur;
+    }
+};
+
+// Stage 1 for one tile: lane t of a team of `team` lanes handles slots
+// t, t + team, ... < count and hands (slot, entry number) to the sink.
+template <class Sink>
+__device__ __forceinline__ void sample_tile(RowSampler& s, int t, int team, int count, Sink&& sink)
+{
+    for (int i = t; i < count; i += team) sink(i, s.next());
+}
+
+// Orders a wave's LDS writes before its later LDS reads (and the reverse for
+// tile reuse).  The hardware executes one wave's LDS operations in order; this
+// only stops the compiler from moving them across.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ---------------------------------------------------------------------------
+// VEC-wide pieces of a row of X / Y
+// ---------------------------------------------------------------------------
+template <int VEC> struct Pack;
+template <> struct Pack<4> {
+    float4 v;
+    __device__ __forceinline__ void zero() { v = make_float4(0.f, 0.f, 0.f, 0.f); }
+    __device__ __forceinline__ void load(const float* p) { v = *reinterpret_cast<const float4*>(p); }
+    __device__ __forceinline__ void store(float* p) const { *reinterpret_cast<float4*>(p) = v; }
+    __device__ __forceinline__ void fma(float a, const Pack& x)
+    {
+        v.x = fmaf(a, x.v.x, v.x); v.y = fmaf(a, x.v.y, v.y);
+        v.z = fmaf(a, x.v.z, v.z); v.w = fmaf(a, x.v.w, v.w);
+    }
+    __device__ __forceinline__ void add_xor(int mask)
+    {
+        v.x += __shfl_xor(v.x, mask, kWaveSize); v.y += __shfl_xor(v.y, mask, kWaveSize);
+        v.z += __shfl_xor(v.z, mask, kWaveSize); v.w += __shfl_xor(v.w, mask, kWaveSize);
+    }
+};
+template <> struct Pack<1> {
+    float v;
+    __device__ __forceinline__ void zero() { v = 0.f; }
+    __device__ __forceinline__ void load(const float* p) { v = *p; }
+    __device__ __forceinline__ void store(float* p) const { *p = v; }
+    __device__ __forceinline__ void fma(float a, const Pack& x) { v = fmaf(a, x.v, v); }
+    __device__ __forceinline__ void add_xor(int mask) { v += __shfl_xor(v, mask, kWaveSize); }
+};
+
+constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v >> 1); }
+
+// ---------------------------------------------------------------------------
+// Fused kernel (Algorithm 1).  G lanes x CH chunks x VEC floats cover one block
+// of G*CH*VEC feature columns (blockIdx.y selects the block).
+// ---------------------------------------------------------------------------
+template <int G, int CH, int VEC>
+__global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
+{
+    constexpr int U = 8 / CH;            // edges in flight per lane
+    constexpr int LOG_G = ilog2(G);
+    using P = Pack<VEC>;
+
+    __shared__ uint2 lds[kWavesPerBlock * kWaveTileStride];
+
+    // XCD-aware remap: hardware deals workgroup b to XCD b % 8; give each XCD a
+    // contiguous run of row blocks.
+    const uint32_t b = blockIdx.x;
+    const uint32_t vb = (b % kNumXcd) * a.blocks_per_xcd + b / kNumXcd;
+    if (vb >= a.nblocks) return;
+
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = threadIdx.x >> 6;
+    const int logR = a.logR;
+    const int team = kWaveSize >> logR;          // lanes per row
+    const int rs = lane >> (6 - logR);           // row slot inside the wave
+    const int t = lane & (team - 1);             // lane inside the team
+    const int e = t >> LOG_G;                    // edge slot
+    const int l = t & (G - 1);                   // column lane
+    const int E = team >> LOG_G;                 // edge slots per row (>= 1)
+    const int T = kTileSlots >> logR;            // tile slots per row
+    uint2* tile = lds + wave * kWaveTileStride + rs * (T + 1);
+
+    const int64_t r = ((((int64_t)vb * kWavesPerBlock) + wave) << logR) + rs;
+    const bool rvalid = r < a.N;
+    int32_t base = 0, n = 0;
+    if (rvalid) {
+        base = a.rowptr[r];
+        n = a.rowptr[r + 1] - base;
+    }
+    const int k = (a.mode == ES_FULL) ? n : min(n, a.W);
+
+    // feature columns of this lane; lanes past F re-read column 0 and are
+    // dropped at the store
+    const int colblk = blockIdx.y * (G * CH * VEC);
+    int coff[CH];
+    bool cok[CH];
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) {
+        const int c = colblk + (ch * G + l) * VEC;
+        cok[ch] = c < a.F;
+        coff[ch] = cok[ch] ? c : 0;
+    }
+
+    RowSampler sampler;
+    sampler.init(a.mode, a.seed, r, (uint32_t)n, (uint32_t)a.W, (uint32_t)t, (uint32_t)team);
+
+    P acc[CH];
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) acc[ch].zero();
+
+    const int32_t* __restrict__ colidx = a.colidx;
+    const float* __restrict__ vals = a.vals;
+    const float* __restrict__ X = a.X;
+    const int64_t ldx = a.ldx;
+
+    for (int t0 = 0; t0 < k; t0 += T) {
+        const int count = min(k - t0, T);
+
+        // ---- stage 1: sample into the tile --------------------------------
+        sample_tile(sampler, t, team, count, [&](int slot, uint32_t entry) {
+            const int64_t p = (int64_t)base + entry;
+            const int32_t c = colidx[p];
+            const float v = vals ? vals[p] : 1.0f;
+            tile[slot] = make_uint2((uint32_t)c, __float_as_uint(v));
+        });
+        wave_lds_fence();
+
+        // ---- stage 2: gather rows of X and accumulate -----------------------
+        int j = e;
+        for (; j + (U - 1) * E < count; j += U * E) {        // full batches
+            uint2 ed[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) ed[u] = tile[j + u * E];
+            P x[U][CH];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float* xr = X + (int64_t)ed[u].x * ldx;
+#pragma unroll
+                for (int ch = 0; ch < CH; ++ch) x[u][ch].load(xr + coff[ch]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float v = __uint_as_float(ed[u].y);
+#pragma unroll
+                for (int ch = 0; ch < CH; ++ch) acc[ch].fma(v, x[u][ch]);
+            }
+        }
+        if (j < count) {                                     // last partial batch
+            uint2 ed[U];
+            bool ok[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int jj = j + u * E;
+                ok[u] = jj < count;
+                ed[u] = tile[ok[u] ? jj : j];                // absent slots re-read a present one
+            }
+            P x[U][CH];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float* xr = X + (int64_t)ed[u].x * ldx;
+#pragma unroll
+                for (int ch = 0; ch < CH; ++ch) x[u][ch].load(xr + coff[ch]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float v = __uint_as_float(ed[u].y);
+                if (ok[u]) {
+#pragma unroll
+                    for (int ch = 0; ch < CH; ++ch) acc[ch].fma(v, x[u][ch]);
+                }
+            }
+        }
+        wave_lds_fence();
+    }
+
+    // ---- sum the E edge slots of each row, store ----------------------------
+    for (int m = G; m < team; m <<= 1) {
+#pragma unroll
+        for (int ch = 0; ch < CH; ++ch) acc[ch].add_xor(m);
+    }
+    if (rvalid && e == 0) {
+        float* y = a.Y + r * (int64_t)a.ldy;
+#pragma unroll
+        for (int ch = 0; ch < CH; ++ch)
+            if (cok[ch]) acc[ch].store(y + coff[ch]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Sampler export: identical team / tile schedule, sink writes CSR positions.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlockThreads)
+es_sample_edges_kernel(const int32_t* __restrict__ rowptr, int64_t N, int32_t W, int32_t mode,
+                       uint64_t seed, int32_t logR, int32_t* __restrict__ pos,
+                       int32_t* __restrict__ cnt)
+{
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = threadIdx.x >> 6;
+    const int team = kWaveSize >> logR;
+    const int rs = lane >> (6 - logR);
+    const int t = lane & (team - 1);
+    const int T = kTileSlots >> logR;
+    const int64_t r = ((((int64_t)blockIdx.x * kWavesPerBlock) + wave) << logR) + rs;
+    if (r >= N) return;
+    const int32_t base = rowptr[r];
+    const int32_t n = rowptr[r + 1] - base;
+    const int k = min(n, W);
+
+    RowSampler sampler;
+    sampler.init(mode, seed, r, (uint32_t)n, (uint32_t)W, (uint32_t)t, (uint32_t)team);
+    int32_t* out = pos + r * (int64_t)W;
+    for (int t0 = 0; t0 < k; t0 += T) {
+        const int count = min(k - t0, T);
+        sample_tile(sampler, t, team, count,
+                    [&](int slot, uint32_t entry) { out[t0 + slot] = base + (int32_t)entry; });
+    }
+    for (int i = k + t; i < W; i += team) out[i] = -1;
+    if (t == 0) cnt[r] = k;
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+struct Shape {
+    int vec, G, CH;
+};
+
+int next_pow2(int v)
+{
+    int p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+
+// Lanes x chunks that cover F columns with VEC-wide accesses.
+Shape pick_shape(int F, bool vec4)
+{
+    Shape s;
+    s.vec = vec4 ? 4 : 1;
+    const int q = (F + s.vec - 1) / s.vec;                 // accesses per row
+    const int gmin = vec4 ? 4 : 16;
+    s.G = next_pow2(q);
+    if (s.G < gmin) s.G = gmin;
+    s.CH = 1;
+    if (s.G > 64) {
+        s.G = 64;
+        s.CH = q > 128 ? 4 : 2;
+    }
+    return s;
+}
+
+// Rows per wave: enough edge slots per row to fill a batch of loads, but not
+// more slots than a typical row has entries.
+int pick_logR(const Shape& s, double mean_kept)
+{
+    const int U = 8 / s.CH;
+    const int maxR = 64 / s.G;
+    if (mean_kept < 1.0) mean_kept = 1.0;
+    const double want = 64.0 * U / (s.G * mean_kept);      // R >= want
+    int R = 1;
+    while (R < maxR && R < want) R <<= 1;
+    int logR = 0;
+    while ((1 << logR) < R) ++logR;
+    return logR;
+}
+
+template <int G, int CH, int VEC>
+hipError_t launch(const Args& a, dim3 grid, hipStream_t st)
+{
+    hipLaunchKernelGGL((es_spmm_kernel<G, CH, VEC>), grid, dim3(kBlockThreads), 0, st, a);
+    return hipGetLastError();
+}
+
+int32_t g_force_logR = -1;   // es_spmm_set_rows_per_wave override; -1 = heuristic
+
+}  // namespace
+
+extern "C" {
+
+const char* es_spmm_status_string(int status)
+{
+    switch (status) {
+        case ES_OK: return "ES_OK";
+        case ES_ERR_INVALID_ARG: return "ES_ERR_INVALID_ARG: null pointer, negative size, ld < F, W < 1 or unknown mode";
+        case ES_ERR_UNSUPPORTED: return "ES_ERR_UNSUPPORTED: shape outside what the kernels cover";
+        case ES_ERR_LAUNCH: return "ES_ERR_LAUNCH: the HIP runtime rejected the launch";
+        default: return "unknown es_spmm status";
+    }
+}
+
+int32_t es_spmm_max_W(int32_t F) { return F < 1 ? 0 : INT32_MAX; }
+
+int32_t es_spmm_tile_slots(int32_t rows_per_wave)
+{
+    if (rows_per_wave == 0) return kTileSlots;
+    if (rows_per_wave < 1 || rows_per_wave > 64 || (rows_per_wave & (rows_per_wave - 1))) return 0;
+    return kTileSlots / rows_per_wave;
+}
+
+int es_spmm_set_rows_per_wave(int32_t rows_per_wave)
+{
+    if (rows_per_wave == 0) { g_force_logR = -1; return ES_OK; }
+    if (rows_per_wave < 1 || rows_per_wave > 64 || (rows_per_wave & (rows_per_wave - 1)))
+        return ES_ERR_INVALID_ARG;
+    int lg = 0;
+    while ((1 << lg) < rows_per_wave) ++lg;
+    g_force_logR = lg;
+    return ES_OK;
+}
+
+int es_spmm(const int32_t* rowptr, const int32_t* colidx, const float* vals, const float* X,
+            float* Y, int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W,
+            int32_t mode, uint64_t seed, void* stream)
+{
+    if (N < 0 || nnz < 0 || nnz > INT32_MAX || F < 1 || ldx < F || ldy < F) return ES_ERR_INVALID_ARG;
+    if (mode != ES_FULL && mode != ES_BUCKET && mode != ES_FASTRAND) return ES_ERR_INVALID_ARG;
+    if (mode != ES_FULL && W < 1) return ES_ERR_INVALID_ARG;
+    if (N == 0) return ES_OK;
+    if (!rowptr || !X || !Y) return ES_ERR_INVALID_ARG;
+    if (nnz > 0 && !colidx) return ES_ERR_INVALID_ARG;
+
+    const bool vec4 = (F % 4 == 0) && (ldx % 4 == 0) && (ldy % 4 == 0) &&
+                      (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
+                      (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
+    const Shape s = pick_shape(F, vec4);
+
+    double mean = (double)nnz / (double)N;
+    if (mode != ES_FULL && mean > (double)W) mean = (double)W;
+    int logR = pick_logR(s, mean);
+    if (g_force_logR >= 0) {
+        logR = g_force_logR;
+        while ((64 >> logR) < s.G) --logR;                 // at least one edge slot per row
+    }
+
+    const int64_t rows_per_block = (int64_t)kWavesPerBlock << logR;
+    const int64_t nblocks = (N + rows_per_block - 1) / rows_per_block;
+    const int64_t per_xcd = (nblocks + kNumXcd - 1) / kNumXcd;
+    const int64_t grid_x = per_xcd * kNumXcd;
+    const int cols_per_block = s.G * s.CH * s.vec;
+    const int64_t grid_y = ((int64_t)F + cols_per_block - 1) / cols_per_block;
+    if (grid_x > INT32_MAX || grid_y > 65535) return ES_ERR_UNSUPPORTED;
+
+    Args a;
+    a.rowptr = rowptr; a.colidx = colidx; a.vals = vals; a.X = X; a.Y = Y;
+    a.N = N; a.seed = seed; a.F = F; a.ldx = ldx; a.ldy = ldy;
+    a.W = (mode == ES_FULL) ? INT32_MAX : W;
+    a.mode = mode; a.logR = logR;
+    a.nblocks = (uint32_t)nblocks; a.blocks_per_xcd = (uint32_t)per_xcd;
+
+    const dim3 grid((uint32_t)grid_x, (uint32_t)grid_y);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t err = hipErrorInvalidValue;
+#define ES_CASE(G_, CH_, V_)                                   \
+    if (s.G == G_ && s.CH == CH_ && s.vec == V_) err = launch<G_, CH_, V_>(a, grid, st);
+    ES_CASE(4, 1, 4) ES_CASE(8, 1, 4) ES_CASE(16, 1, 4) ES_CASE(32, 1, 4)
+    ES_CASE(64, 1, 4) ES_CASE(64, 2, 4) ES_CASE(64, 4, 4)
+    ES_CASE(16, 1, 1) ES_CASE(32, 1, 1) ES_CASE(64, 1, 1) ES_CASE(64, 2, 1) ES_CASE(64, 4, 1)
+#undef ES_CASE
+    return err == hipSuccess ? ES_OK : ES_ERR_LAUNCH;
+}
+
+int es_spmm_sample_edges(const int32_t* rowptr, int64_t N, int32_t W, int32_t mode, uint64_t seed,
+                         int32_t rows_per_wave, int32_t* pos, int32_t* cnt, void* stream)
+{
+    if (N < 0 || W < 1) return ES_ERR_INVALID_ARG;
+    if (mode != ES_BUCKET && mode != ES_FASTRAND) return ES_ERR_INVALID_ARG;
+    if (rows_per_wave < 0 || rows_per_wave > 64 || (rows_per_wave & (rows_per_wave - 1)))
+        return ES_ERR_INVALID_ARG;
+    if (N == 0) return ES_OK;
+    if (!rowptr || !pos || !cnt) return ES_ERR_INVALID_ARG;
+    if (N * (int64_t)W > INT32_MAX) return ES_ERR_UNSUPPORTED;
+    int logR = 0;
+    while ((1 << logR) < rows_per_wave) ++logR;
+    const int64_t rows_per_block = (int64_t)kWavesPerBlock << logR;
+    const int64_t nblocks = (N + rows_per_block - 1) / rows_per_block;
+    if (nblocks > INT32_MAX) return ES_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(es_sample_edges_kernel, dim3((uint32_t)nblocks), dim3(kBlockThreads), 0,
+                       static_cast<hipStream_t>(stream), rowptr, N, W, mode, seed, logR, pos, cnt);
+    return hipGetLastError() == hipSuccess ? ES_OK : ES_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,72 @@
+"""Helpers shared by the GPU parity tests: upload a workload, run the HIP path
+through the C ABI, compare with the CPU oracle."""
+import numpy as np
+
+TOL = 1e-5      # max |Y_gpu - Y_ref| / sum_kept |a_ij| |x_j|  (the build's stated bound)
+
+
+class DeviceCSR:
+    def __init__(self, rowptr, colidx, vals, X, F=None, device="cuda:0"):
+        import torch
+        self.h_rowptr, self.h_colidx, self.h_vals, self.h_X = rowptr, colidx, vals, X
+        self.rowptr = torch.from_numpy(rowptr).to(device)
+        self.colidx = torch.from_numpy(colidx).to(device)
+        self.vals = None if vals is None else torch.from_numpy(vals).to(device)
+        self.X = torch.from_numpy(X).to(device)
+        self.N = rowptr.shape[0] - 1
+        self.F = X.shape[1] if F is None else F
+
+    def run(self, W, mode, seed=0, ldy=None):
+        import torch
+        import paper_2104_10716_amd as es
+        ldy = self.F if ldy is None else ldy
+        Y = torch.full((self.N, ldy), float("nan"), dtype=torch.float32, device=self.X.device)
+        es.es_spmm(self.rowptr, self.colidx, self.vals, self.X, Y, W, mode, seed, F=self.F)
+        torch.cuda.synchronize()
+        return Y
+
+    def edges(self, W, mode, seed=0, rows_per_wave=0):
+        import torch
+        import paper_2104_10716_amd as es
+        pos, cnt = es.es_spmm_sample_edges(self.rowptr, W, mode, seed, rows_per_wave)
+        torch.cuda.synchronize()
+        return pos, cnt
+
+
+def check_Y(Y_gpu, Yref, denom, what, tol=TOL):
+    """|Y_gpu - Yref| <= tol * denom element-wise (so denom == 0 demands an exact 0)."""
+    Yg = np.asarray(Y_gpu, dtype=np.float64)
+    assert Yg.shape == Yref.shape, (what, Yg.shape, Yref.shape)
+    assert np.isfinite(Yg).all(), f"{what}: non-finite output (unwritten rows?)"
+    err = np.abs(Yg - Yref)
+    bad = err > tol * denom
+    if bad.any():
+        i = np.unravel_index(np.argmax(err - tol * denom), err.shape)
+        raise AssertionError(f"{what}: {int(bad.sum())} of {bad.size} elements out of tolerance; "
+                             f"worst at {i}: gpu={Yg[i]!r} ref={Yref[i]!r} denom={denom[i]!r}")
+    with np.errstate(divide="ignore", invalid="ignore"):
+        rel = np.where(denom > 0, err / denom, 0.0)
+    return float(rel.max()) if rel.size else 0.0
+
+
+def check_against_oracle(d, W, mode, seed=0, rows=None, ldy=None, what=""):
+    """Run es_spmm on DeviceCSR `d` and compare (all rows, or the listed rows)."""
+    import oracle
+    Y = d.run(W, mode, seed, ldy=ldy)
+    Yh = Y.cpu().numpy()
+    if ldy is not None and ldy > d.F:
+        assert np.isnan(Yh[:, d.F:]).all(), f"{what}: columns beyond F were written"
+    Yh = Yh[:, :d.F]
+    Yref, den = oracle.spmm(d.h_rowptr, d.h_colidx, d.h_vals, d.h_X, d.F, W, mode, seed, rows=rows)
+    if rows is not None:
+        Yh = Yh[np.asarray(rows)]
+    return check_Y(Yh, Yref, den, what or f"{mode} W={W} seed={seed}")
+
+
+def check_edges(d, W, mode, seed=0, rows_per_wave=0, what=""):
+    import oracle
+    pos, cnt = d.edges(W, mode, seed, rows_per_wave)
+    opos, ocnt = oracle.kept(d.h_rowptr, W, mode, seed)
+    what = what or f"{mode} W={W} seed={seed} rpw={rows_per_wave}"
+    assert np.array_equal(cnt.cpu().numpy(), ocnt), f"{what}: kept counts differ"
+    assert np.array_equal(pos.cpu().numpy(), opos), f"{what}: sampled edge lists differ"
