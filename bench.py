@@ -1,0 +1,317 @@
+#!/usr/bin/env python3
+"""Benchmark of the ES-SpMM hot path on one MI355X.
+
+A *step* is one pass of the whole hot path over one synthetic graph: for every
+sampling width W of the configuration, es_spmm in bucket and in fastrand mode,
+plus the full (unsampled) product -- Algorithm 1 of the paper end to end, and
+the exact CSR SpMM it is compared with.  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|3|4]
+                    [--main-only] [--no-cpu-baseline]
+
+value         = sum of algorithmic bytes of the step / wall time of the step
+algorithmic   = 4(N+1) + 8 nnz_kept + 4 F nnz_kept + 4 F N   bytes per call
+                (row pointers, sampled column+value pairs, one row of X per
+                kept entry, Y written once)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+# HBM bytes per launch of the dominant kernel (mean over the launches of one
+# step) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a copy
+# kernel of known size; filled in from the summaries under profiles/.
+MEASURED_TRAFFIC_BYTES = {
+}
+
+CONFIG_TEXT = {
+    2: "configs[1] mid-size citation-like graph: N=170k, power-law degree mean 14, F=128",
+    3: "configs[2] dense social-like graph: N=233k, power-law degree mean 490, F=64",
+    4: "configs[3] large co-purchase-like graph: N=2.45M, mean degree 50, F=128 (100 padded)",
+}
+
+
+def log(msg: str) -> None:
+    print(msg, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(N: int, nnz_kept: int, F: int) -> int:
+    return 4 * (N + 1) + 8 * nnz_kept + 4 * F * nnz_kept + 4 * F * N
+
+
+class DeviceWorkload:
+    def __init__(self, w, dev, X=None, F=None):
+        import numpy as np
+        import torch
+        self.w = w
+        self.N, self.nnz = w.N, w.nnz
+        self.F = w.F if F is None else F
+        self.deg = np.diff(w.rowptr).astype(np.int64)
+        self.rowptr = torch.from_numpy(w.rowptr).to(dev)
+        self.colidx = torch.from_numpy(w.colidx).to(dev)
+        self.vals = torch.from_numpy(w.vals).to(dev)
+        self.X = torch.from_numpy(w.X).to(dev) if X is None else X
+        self.Y = torch.empty((self.N, self.F), dtype=torch.float32, device=dev)
+
+    def calls(self, Ws):
+        out = []
+        for W in Ws:
+            for mode in ("bucket", "fastrand"):
+                out.append((mode, int(W)))
+        out.append(("full", 0))
+        return out
+
+    def nnz_kept(self, mode, W):
+        import numpy as np
+        return int(self.nnz if mode == "full" else np.minimum(self.deg, W).sum())
+
+    def launch(self, mode, W, seed=0):
+        import paper_2104_10716_amd as es
+        es.es_spmm(self.rowptr, self.colidx, self.vals, self.X, self.Y, W, mode, seed, F=self.F)
+
+
+def time_call(dw, mode, W, reps, flush=None):
+    """Median / min ms of one es_spmm call from HIP events on the launch stream."""
+    import torch
+    ts = []
+    for _ in range(reps):
+        if flush is not None:
+            flush.add_(1.0)
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        dw.launch(mode, W)
+        b.record()
+        b.synchronize()
+        ts.append(a.elapsed_time(b))
+    ts.sort()
+    return ts[len(ts) // 2], ts[0]
+
+
+def per_call_table(dw, calls, reps, flush, cold_reps):
+    rows = []
+    t_full = None
+    for mode, W in calls:
+        for _ in range(2):
+            dw.launch(mode, W)
+        med, mn = time_call(dw, mode, W, reps)
+        cold = time_call(dw, mode, W, cold_reps, flush)[0] if flush is not None else None
+        kept = dw.nnz_kept(mode, W)
+        B = algorithmic_bytes(dw.N, kept, dw.F)
+        rows.append({"mode": mode, "W": W, "nnz_kept": kept, "ms": round(med, 4), "ms_min": round(mn, 4),
+                     "ms_cold": None if cold is None else round(cold, 4),
+                     "gflops": round(2.0 * kept * dw.F / (med * 1e6), 1),
+                     "eff_GBps": round(B / (med * 1e6), 1),
+                     "frac_hbm_peak": round(B / (med * 1e6) / HBM_PEAK_GBPS, 4),
+                     "eff_GBps_cold": None if cold is None else round(B / (cold * 1e6), 1)})
+        if mode == "full":
+            t_full = med
+    for r in rows:
+        r["speedup_vs_full"] = round(t_full / r["ms"], 2) if t_full else None
+    return rows
+
+
+def cpu_baseline(dw, calls):
+    """The CPU oracle, as it stands, on one whole step of the same workload."""
+    import oracle
+    w = dw.w
+    X = w.X
+    t0 = time.perf_counter()
+    total_bytes = 0
+    for mode, W in calls:
+        oracle.spmm(w.rowptr, w.colidx, w.vals, X, dw.F, W, mode, 0, want_denom=False)
+        total_bytes += algorithmic_bytes(dw.N, dw.nnz_kept(mode, W), dw.F)
+    dt = time.perf_counter() - t0
+    return {"value": round(total_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.threads(),
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": "one whole step (every call of the sweep, all rows), fp64 accumulation"}
+
+
+def cpu_baseline_rows(dw, calls, target_seconds=20.0):
+    """For the large graphs: the oracle on a bounded random subset of rows."""
+    import numpy as np
+    import oracle
+    w = dw.w
+    work = sum(dw.nnz_kept(m, W) for m, W in calls) * dw.F
+    frac = min(1.0, target_seconds * 1.0e9 / max(work, 1))     # ~1 G fp64 FMA per second assumed
+    nrows = max(1, int(dw.N * frac))
+    rows = np.sort(np.random.default_rng(0).choice(dw.N, size=nrows, replace=False)).astype(np.int64)
+    t0 = time.perf_counter()
+    total_bytes = 0
+    for mode, W in calls:
+        oracle.spmm(w.rowptr, w.colidx, w.vals, w.X, dw.F, W, mode, 0, rows=rows, want_denom=False)
+        kept = int((dw.deg[rows] if mode == "full" else np.minimum(dw.deg[rows], W)).sum())
+        total_bytes += algorithmic_bytes(nrows, kept, dw.F)
+    dt = time.perf_counter() - t0
+    return {"value": round(total_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.threads(),
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": f"{nrows} random rows of {dw.N} ({100.0 * nrows / dw.N:.1f}%), every call of the sweep"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, choices=(2, 3, 4))
+    ap.add_argument("--main-only", action="store_true",
+                    help="only the timed sweep of --config (what the rocprofv3 summaries profile)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three 1 GiB device-to-device copies (a kernel of known traffic "
+                         "to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (rows of A shard across GPUs by design, "
+              "but no multi-GPU path is built); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2104_10716_amd as es
+    from workloads import make_workload
+    es.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+
+    t0 = time.perf_counter()
+    w = make_workload(args.config)
+    log(f"config {args.config}: N={w.N} nnz={w.nnz} F={w.F} generated in {time.perf_counter() - t0:.1f}s")
+    dw = DeviceWorkload(w, dev)
+    calls = dw.calls(w.Ws)
+    step_bytes = sum(algorithmic_bytes(dw.N, dw.nnz_kept(m, W), dw.F) for m, W in calls)
+    step_flops = sum(2 * dw.nnz_kept(m, W) * dw.F for m, W in calls)
+
+    def step():
+        for mode, W in calls:
+            dw.launch(mode, W)
+
+    if args.calibrate_copy:
+        src = torch.ones(256 * 1024 * 1024, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = ev0.elapsed_time(ev1)
+    ms_per_step = wall * 1e3 / args.steps
+    launches = args.steps * len(calls)
+    kernel_ms = ev_ms / launches                      # mean launch duration, HIP events
+    bytes_per_launch = step_bytes / len(calls)
+    achieved = bytes_per_launch / (kernel_ms * 1e6)   # GB/s
+    log(f"step: {ms_per_step:.3f} ms wall, {ev_ms / args.steps:.3f} ms by events, "
+        f"{step_bytes / 1e9:.3f} GB algorithmic -> {step_bytes / (ms_per_step * 1e6):.0f} GB/s")
+
+    result = {
+        "metric": "es_spmm effective HBM bandwidth (algorithmic bytes / time) over the W sweep "
+                  "{bucket,fastrand} + full SpMM",
+        "value": round(step_bytes / (ms_per_step * 1e6), 1),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "gflops": round(step_flops / (ms_per_step * 1e6), 1),
+        "config": {"workload": CONFIG_TEXT[args.config], "N": dw.N, "nnz": dw.nnz, "F": dw.F,
+                   "W": list(w.Ws), "modes": ["bucket", "fastrand", "full"], "seed": 0,
+                   "calls_per_step": len(calls)},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
+                     "kernel": "es_spmm_kernel", "launch_ms": round(kernel_ms, 5),
+                     "bytes_per_launch": int(bytes_per_launch)},
+    }
+
+    if not args.main_only:
+        flush = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device=dev)   # 1 GiB
+        flush.zero_()
+        result["calls"] = per_call_table(dw, calls, 20, flush, 5)
+        if not args.no_cpu_baseline:
+            result["cpu_baseline"] = (cpu_baseline(dw, calls) if args.config == 2
+                                      else cpu_baseline_rows(dw, calls))
+            log(f"cpu baseline: {result['cpu_baseline']}")
+        extra = []
+        for cfg in (3, 4):
+            if cfg == args.config:
+                continue
+            del dw
+            torch.cuda.empty_cache()
+            t0 = time.perf_counter()
+            w = make_workload(cfg)
+            log(f"config {cfg}: N={w.N} nnz={w.nnz} F={w.F} generated in {time.perf_counter() - t0:.1f}s")
+            dw = DeviceWorkload(w, dev)
+            rows = per_call_table(dw, dw.calls(w.Ws), 10, flush, 3)
+            extra.append({"workload": CONFIG_TEXT[cfg], "N": dw.N, "nnz": dw.nnz, "F": dw.F, "calls": rows})
+            for r in rows:
+                log(f"  cfg{cfg} {r['mode']:8s} W={r['W']:4d}: {r['ms']:.3f} ms  {r['eff_GBps']:.0f} GB/s "
+                    f"({100 * r['frac_hbm_peak']:.1f}% of peak)  cold {r['ms_cold']} ms  x{r['speedup_vs_full']} vs full")
+            if cfg == 3:
+                extra.append(gcn_feature_sweep(dw, dev, flush))
+        result["extra"] = extra
+    elif not args.no_cpu_baseline:
+        result["cpu_baseline"] = (cpu_baseline(dw, calls) if args.config == 2
+                                  else cpu_baseline_rows(dw, calls))
+
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def gcn_feature_sweep(dw3, dev, flush):
+    """configs[4]: the SpMM stages of a 2-layer GCN forward on the config-3
+    graph, H1 = relu(A (X0 W1)) at F = 256 and out = A (H1 W2) at F = 41; the
+    dense products are torch GEMMs and are not timed."""
+    import torch
+    from workloads import gcn_operands
+    X0h, W1h, W2h = gcn_operands(dw3.N)
+    X0 = torch.from_numpy(X0h).to(dev)
+    W1 = torch.from_numpy(W1h).to(dev)
+    W2 = torch.from_numpy(W2h).to(dev)
+    Z1 = X0 @ W1
+    del X0
+    out = {"workload": "configs[4] 2-layer GCN forward on the config-3 graph, SpMM stages only",
+           "N": dw3.N, "nnz": dw3.nnz, "stages": []}
+    for mode, W in (("bucket", 64), ("fastrand", 64), ("full", 0)):
+        d1 = DeviceWorkload(dw3.w, dev, X=Z1, F=256)
+        r1 = per_call_table(d1, [(mode, W)], 10, flush, 3)[0]
+        H1 = torch.relu(d1.Y)
+        Z2 = H1 @ W2                                        # [N x 41], row stride 41
+        d2 = DeviceWorkload(dw3.w, dev, X=Z2, F=41)
+        r2 = per_call_table(d2, [(mode, W)], 10, flush, 3)[0]
+        for F, r in ((256, r1), (41, r2)):
+            r = dict(r, F=F)
+            r.pop("speedup_vs_full", None)
+            out["stages"].append(r)
+            log(f"  cfg5 F={F:3d} {mode:8s} W={W:3d}: {r['ms']:.3f} ms  {r['eff_GBps']:.0f} GB/s "
+                f"({100 * r['frac_hbm_peak']:.1f}% of peak)")
+        del d1, d2, H1, Z2
+    full = {s["F"]: s["ms"] for s in out["stages"] if s["mode"] == "full"}
+    for s in out["stages"]:
+        s["speedup_vs_full"] = round(full[s["F"]] / s["ms"], 2)
+    return out
+
+
+if __name__ == "__main__":
+    sys.exit(main())

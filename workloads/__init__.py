@@ -10,6 +10,7 @@ from .graphs import (  # noqa: F401
     Workload,
     make_workload,
     csr_from_degrees,
+    gcn_operands,
     powerlaw_degrees,
     random_csr,
 )

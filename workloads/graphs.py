@@ -232,6 +232,16 @@ def _cfg4(scale: float) -> Workload:
     return Workload(4, "copurchase-like", rowptr, colidx, vals, X, 128, (32, 64, 128))
 
 
+def gcn_operands(n: int):
+    """Dense operands of config 5 for an n-node graph: X0 [n x 602] uniform[-1,1],
+    W1 [602 x 256] and W2 [256 x 41] Glorot-uniform."""
+    X0 = _uniform_pm1(np.random.default_rng(_FEAT_SEED + 5), (n, 602))
+    wrng = np.random.default_rng(_WEIGHT_SEED + 5)
+    W1 = _glorot(wrng, 602, 256)
+    W2 = _glorot(wrng, 256, 41)
+    return X0, W1, W2
+
+
 def _cfg5(scale: float) -> Workload:
     """Config-3 graph plus the dense operands of a 2-layer GCN forward.  `X` is
     the first layer's input X0 [N x 602]; `extras` holds W1 [602 x 256] and
@@ -239,10 +249,7 @@ def _cfg5(scale: float) -> Workload:
     relu(.)*W2 (F=41); the caller forms those products."""
     n, rowptr, colidx = _cfg3_graph(scale)
     vals = mean_agg_vals(rowptr)
-    X0 = _uniform_pm1(np.random.default_rng(_FEAT_SEED + 5), (n, 602))
-    wrng = np.random.default_rng(_WEIGHT_SEED + 5)
-    W1 = _glorot(wrng, 602, 256)
-    W2 = _glorot(wrng, 256, 41)
+    X0, W1, W2 = gcn_operands(n)
     return Workload(5, "gcn2-feature-sweep", rowptr, colidx, vals, X0, 602, (64,),
                     extras={"W1": W1, "W2": W2})
 
