@@ -83,9 +83,10 @@ int es_spmm(const int32_t* rowptr, const int32_t* colidx, const float* vals,
  * rowptr[r] + (entry number of slot i) into pos[r * W + i]; slots i >= k_r get
  * -1; cnt[r] = k_r = min(n_r, W).  mode must be ES_BUCKET or ES_FASTRAND.
  *   pos [N * W] int32 (device), cnt [N] int32 (device); N * W must be < 2^31.
- *   rows_per_wave: 0 = the library's default schedule, else a power of two in
- *   [1, 64] forcing how many rows share a wavefront (every value must produce
- *   the same output; tests sweep it).
+ *   rows_per_wave: 0 = the library's default schedule, a power of two in
+ *   [1, 64] = that many rows share a wavefront, -1 = the long-row schedule (a
+ *   whole wavefront per row, the sampler restarted at every 512-slot segment).
+ *   Every value must produce the same output; tests sweep it.
  */
 int es_spmm_sample_edges(const int32_t* rowptr, int64_t N, int32_t W, int32_t mode,
                          uint64_t seed, int32_t rows_per_wave,
@@ -112,6 +113,18 @@ int32_t es_spmm_tile_slots(int32_t rows_per_wave);
  * same sampled edges; Y differs only by fp32 summation order.
  */
 int es_spmm_set_rows_per_wave(int32_t rows_per_wave);
+
+/*
+ * Long-row threshold override.  A row keeping more than `entries` sampled
+ * entries is not summed by one wavefront but cut into 512-entry segments that
+ * several workgroups process in parallel (load balance for the skewed degree
+ * distributions Section 4.5 "load balancing" describes; sampled rows never
+ * exceed W, so this matters for ES_FULL and for very large W).  0 restores the
+ * built-in choice (derived from nnz, F and the launch shape); any positive
+ * value is legal.
+ * Process-wide, not thread-safe; for tuning sweeps and tests.
+ */
+int es_spmm_set_long_row_threshold(int32_t entries);
 
 #ifdef __cplusplus
 }

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     es_spmm,
     es_spmm_max_W,
     es_spmm_sample_edges,
+    es_spmm_set_long_row_threshold,
     es_spmm_set_rows_per_wave,
     es_spmm_status_string,
     es_spmm_tile_slots,

@@ -19,6 +19,13 @@
 //     ordering is needed because a tile is private to its wave.
 //   * Workgroup ids are remapped so each of the 8 XCDs (one L2 each) walks one
 //     contiguous range of rows.
+//   * Rows that keep more than `long_k` entries (full mode on skewed graphs, or a
+//     very large W) would leave one wave running long after the rest of the grid
+//     has drained.  The row kernel stores zeros for them and a second kernel
+//     splits each such row into 512-slot segments, deals the segments to the
+//     waves of kLongSplit workgroups and adds the partial sums to Y with fp32
+//     atomics.  long_k is chosen on the host so that a single wave's longest row
+//     stays a few percent of the whole launch.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -32,6 +39,8 @@ constexpr int kBlockThreads = kWaveSize * kWavesPerBlock;
 constexpr int kTileSlots = 512;                       // (col, val) slots per wave
 constexpr int kWaveTileStride = kTileSlots + 64;      // + one pad slot per row slot
 constexpr int kNumXcd = 8;
+constexpr int kLongScanRows = 1024;                   // rows one long-row workgroup scans
+constexpr int kLongSplit = 16;                        // workgroups sharing those rows
 
 struct Args {
     const int32_t* rowptr;
@@ -42,6 +51,7 @@ struct Args {
     int64_t N;
     uint64_t seed;
     int32_t F, ldx, ldy, W, mode, logR;
+    int32_t long_k;            // rows keeping more entries go to the long-row kernel
     uint32_t nblocks;          // workgroups that carry rows
     uint32_t blocks_per_xcd;   // ceil(nblocks / 8)
 };
@@ -67,7 +77,7 @@ struct RowSampler {
     uint32_t step;   // increment per call, already reduced mod n
     uint32_t wrap;   // n for FastRand, 0xFFFFFFFF when no wrap can happen
 
-    // requires first < 65536 and stride <= 64
+    // requires stride <= 64
     __device__ __forceinline__ void init(int mode, uint64_t seed, int64_t row, uint32_t n,
                                          uint32_t W, uint32_t first, uint32_t stride)
     {
@@ -81,7 +91,10 @@ struct RowSampler {
         uint32_t off = 0;
         if (seed != 0)
             off = (uint32_t)(splitmix64_output(seed, (uint64_t)row + 1u) >> 32) % n;
-        idx = (uint32_t)(((uint64_t)off + (uint64_t)first * P) % n);
+        if (first < 65536u)
+            idx = (off + (first * P) % n) % n;               // both terms < n < 2^31
+        else
+            idx = (uint32_t)(((uint64_t)off + (uint64_t)first * P) % n);
         step = (stride * P) % n;
         wrap = n;
     }
@@ -133,6 +146,11 @@ template <> struct Pack<4> {
         v.x += __shfl_xor(v.x, mask, kWaveSize); v.y += __shfl_xor(v.y, mask, kWaveSize);
         v.z += __shfl_xor(v.z, mask, kWaveSize); v.w += __shfl_xor(v.w, mask, kWaveSize);
     }
+    __device__ __forceinline__ void atomic_add(float* p) const
+    {
+        unsafeAtomicAdd(p, v.x); unsafeAtomicAdd(p + 1, v.y);
+        unsafeAtomicAdd(p + 2, v.z); unsafeAtomicAdd(p + 3, v.w);
+    }
 };
 template <> struct Pack<1> {
     float v;
@@ -141,9 +159,102 @@ template <> struct Pack<1> {
     __device__ __forceinline__ void store(float* p) const { *p = v; }
     __device__ __forceinline__ void fma(float a, const Pack& x) { v = fmaf(a, x.v, v); }
     __device__ __forceinline__ void add_xor(int mask) { v += __shfl_xor(v, mask, kWaveSize); }
+    __device__ __forceinline__ void atomic_add(float* p) const { unsafeAtomicAdd(p, v); }
 };
 
 constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v >> 1); }
+
+// Feature columns one lane covers: CH chunks of VEC floats, chunk ch at column
+// colblk + (ch*G + l)*VEC.  Lanes past F re-read column 0 and never store.
+template <int G, int CH, int VEC>
+struct LaneCols {
+    int off[CH];
+    bool ok[CH];
+    __device__ __forceinline__ void init(int colblk, int l, int F)
+    {
+#pragma unroll
+        for (int ch = 0; ch < CH; ++ch) {
+            const int c = colblk + (ch * G + l) * VEC;
+            ok[ch] = c < F;
+            off[ch] = ok[ch] ? c : 0;
+        }
+    }
+};
+
+// Stage 1 of Algorithm 1 for one tile: copy the sampled (column, value) pairs
+// of slots [0, count) into the LDS tile.
+__device__ __forceinline__ void stage_tile(RowSampler& sampler, int t, int team, int count,
+                                           int32_t base, const int32_t* __restrict__ colidx,
+                                           const float* __restrict__ vals, uint2* tile)
+{
+    sample_tile(sampler, t, team, count, [&](int slot, uint32_t entry) {
+        const int64_t p = (int64_t)base + entry;
+        const int32_t c = colidx[p];
+        const float v = vals ? vals[p] : 1.0f;
+        tile[slot] = make_uint2((uint32_t)c, __float_as_uint(v));
+    });
+}
+
+// Stage 2 of Algorithm 1 for one tile: this lane's edge slot e (of E) walks
+// tile entries e, e+E, ... < count, U at a time: U LDS broadcasts, then U*CH
+// independent loads of X, then the FMAs.
+template <int G, int CH, int VEC>
+__device__ __forceinline__ void consume_tile(const uint2* tile, int count, int e, int E,
+                                             const float* __restrict__ X, int64_t ldx,
+                                             const LaneCols<G, CH, VEC>& cols, Pack<VEC> (&acc)[CH])
+{
+    constexpr int U = 8 / CH;
+    using P = Pack<VEC>;
+    int j = e;
+    for (; j + (U - 1) * E < count; j += U * E) {            // full batches
+        uint2 ed[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) ed[u] = tile[j + u * E];
+        P x[U][CH];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float* xr = X + (int64_t)ed[u].x * ldx;
+#pragma unroll
+            for (int ch = 0; ch < CH; ++ch) x[u][ch].load(xr + cols.off[ch]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float v = __uint_as_float(ed[u].y);
+#pragma unroll
+            for (int ch = 0; ch < CH; ++ch) acc[ch].fma(v, x[u][ch]);
+        }
+    }
+    if (j < count) {                                         // last partial batch
+        uint2 ed[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int jj = j + u * E;
+            ok[u] = jj < count;
+            ed[u] = tile[ok[u] ? jj : j];                    // absent slots re-read a present one
+        }
+        P x[U][CH];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float* xr = X + (int64_t)ed[u].x * ldx;
+#pragma unroll
+            for (int ch = 0; ch < CH; ++ch) x[u][ch].load(xr + cols.off[ch]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float v = __uint_as_float(ed[u].y);
+            if (ok[u]) {
+#pragma unroll
+                for (int ch = 0; ch < CH; ++ch) acc[ch].fma(v, x[u][ch]);
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ int kept_count(int mode, int n, int W)
+{
+    return (mode == ES_FULL) ? n : min(n, W);
+}
 
 // ---------------------------------------------------------------------------
 // Fused kernel (Algorithm 1).  G lanes x CH chunks x VEC floats cover one block
@@ -152,7 +263,6 @@ constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v >> 1); }
 template <int G, int CH, int VEC>
 __global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
 {
-    constexpr int U = 8 / CH;            // edges in flight per lane
     constexpr int LOG_G = ilog2(G);
     using P = Pack<VEC>;
 
@@ -183,19 +293,11 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
         base = a.rowptr[r];
         n = a.rowptr[r + 1] - base;
     }
-    const int k = (a.mode == ES_FULL) ? n : min(n, a.W);
+    int k = kept_count(a.mode, n, a.W);
+    if (k > a.long_k) k = 0;                     // long-row kernel adds this row; store zeros here
 
-    // feature columns of this lane; lanes past F re-read column 0 and are
-    // dropped at the store
-    const int colblk = blockIdx.y * (G * CH * VEC);
-    int coff[CH];
-    bool cok[CH];
-#pragma unroll
-    for (int ch = 0; ch < CH; ++ch) {
-        const int c = colblk + (ch * G + l) * VEC;
-        cok[ch] = c < a.F;
-        coff[ch] = cok[ch] ? c : 0;
-    }
+    LaneCols<G, CH, VEC> cols;
+    cols.init(blockIdx.y * (G * CH * VEC), l, a.F);
 
     RowSampler sampler;
     sampler.init(a.mode, a.seed, r, (uint32_t)n, (uint32_t)a.W, (uint32_t)t, (uint32_t)team);
@@ -204,68 +306,11 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
 #pragma unroll
     for (int ch = 0; ch < CH; ++ch) acc[ch].zero();
 
-    const int32_t* __restrict__ colidx = a.colidx;
-    const float* __restrict__ vals = a.vals;
-    const float* __restrict__ X = a.X;
-    const int64_t ldx = a.ldx;
-
     for (int t0 = 0; t0 < k; t0 += T) {
         const int count = min(k - t0, T);
-
-        // ---- stage 1: sample into the tile --------------------------------
-        sample_tile(sampler, t, team, count, [&](int slot, uint32_t entry) {
-            const int64_t p = (int64_t)base + entry;
-            const int32_t c = colidx[p];
-            const float v = vals ? vals[p] : 1.0f;
-            tile[slot] = make_uint2((uint32_t)c, __float_as_uint(v));
-        });
+        stage_tile(sampler, t, team, count, base, a.colidx, a.vals, tile);
         wave_lds_fence();
-
-        // ---- stage 2: gather rows of X and accumulate -----------------------
-        int j = e;
-        for (; j + (U - 1) * E < count; j += U * E) {        // full batches
-            uint2 ed[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) ed[u] = tile[j + u * E];
-            P x[U][CH];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const float* xr = X + (int64_t)ed[u].x * ldx;
-#pragma unroll
-                for (int ch = 0; ch < CH; ++ch) x[u][ch].load(xr + coff[ch]);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const float v = __uint_as_float(ed[u].y);
-#pragma unroll
-                for (int ch = 0; ch < CH; ++ch) acc[ch].fma(v, x[u][ch]);
-            }
-        }
-        if (j < count) {                                     // last partial batch
-            uint2 ed[U];
-            bool ok[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int jj = j + u * E;
-                ok[u] = jj < count;
-                ed[u] = tile[ok[u] ? jj : j];                // absent slots re-read a present one
-            }
-            P x[U][CH];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const float* xr = X + (int64_t)ed[u].x * ldx;
-#pragma unroll
-                for (int ch = 0; ch < CH; ++ch) x[u][ch].load(xr + coff[ch]);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const float v = __uint_as_float(ed[u].y);
-                if (ok[u]) {
-#pragma unroll
-                    for (int ch = 0; ch < CH; ++ch) acc[ch].fma(v, x[u][ch]);
-                }
-            }
-        }
+        consume_tile<G, CH, VEC>(tile, count, e, E, a.X, a.ldx, cols, acc);
         wave_lds_fence();
     }
 
@@ -278,12 +323,117 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
         float* y = a.Y + r * (int64_t)a.ldy;
 #pragma unroll
         for (int ch = 0; ch < CH; ++ch)
-            if (cok[ch]) acc[ch].store(y + coff[ch]);
+            if (cols.ok[ch]) acc[ch].store(y + cols.off[ch]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Long rows.  Workgroup (bx, by) scans rows [bx*1024, bx*1024+1024) for rows
+// that keep more than long_k entries, numbers their 512-slot segments with a
+// prefix sum in LDS, and its 4 waves take segments gw, gw + 4*kLongSplit, ...
+// (gw = by*4 + wave).  A segment is one pass of Algorithm 1 with a whole wave on
+// the row; its partial sums are added to Y (zeroed by the row kernel) with
+// fp32 atomics, so the summation order across segments is not fixed.
+// ---------------------------------------------------------------------------
+template <int G, int CH, int VEC>
+__global__ void __launch_bounds__(kBlockThreads) es_spmm_long_rows_kernel(const Args a)
+{
+    constexpr int LOG_G = ilog2(G);
+    constexpr int kRowsPerThread = kLongScanRows / kBlockThreads;
+    using P = Pack<VEC>;
+
+    __shared__ uint2 lds[kWavesPerBlock * kWaveTileStride];
+    __shared__ int seg_end[kLongScanRows];       // inclusive prefix sum of segment counts
+    __shared__ int wave_total[kWavesPerBlock];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWaveSize - 1);
+    const int wave = tid >> 6;
+    const int64_t row0 = (int64_t)blockIdx.x * kLongScanRows;
+
+    // thread tid owns rows row0 + tid*kRowsPerThread + i (consecutive, so the
+    // prefix order is the row order)
+    int nseg[kRowsPerThread];
+    int mine = 0;
+#pragma unroll
+    for (int i = 0; i < kRowsPerThread; ++i) {
+        const int64_t r = row0 + tid * kRowsPerThread + i;
+        nseg[i] = 0;
+        if (r < a.N) {
+            const int n = a.rowptr[r + 1] - a.rowptr[r];
+            const int k = kept_count(a.mode, n, a.W);
+            if (k > a.long_k) nseg[i] = (k + kTileSlots - 1) / kTileSlots;
+        }
+        mine += nseg[i];
+    }
+    int incl = mine;                             // inclusive scan inside the wave
+#pragma unroll
+    for (int d = 1; d < kWaveSize; d <<= 1) {
+        const int up = __shfl_up(incl, d, kWaveSize);
+        if (lane >= d) incl += up;
+    }
+    if (lane == kWaveSize - 1) wave_total[wave] = incl;
+    __syncthreads();
+    int before = incl - mine;
+    for (int w = 0; w < wave; ++w) before += wave_total[w];
+#pragma unroll
+    for (int i = 0; i < kRowsPerThread; ++i) {
+        before += nseg[i];
+        seg_end[tid * kRowsPerThread + i] = before;
+    }
+    __syncthreads();
+    const int total = seg_end[kLongScanRows - 1];
+    if (total == 0) return;
+
+    const int e = lane >> LOG_G;
+    const int l = lane & (G - 1);
+    constexpr int E = kWaveSize / G;
+    uint2* tile = lds + wave * kWaveTileStride;
+    LaneCols<G, CH, VEC> cols;
+    cols.init(blockIdx.z * (G * CH * VEC), l, a.F);
+
+    const int gw = blockIdx.y * kWavesPerBlock + wave;
+    for (int task = gw; task < total; task += kLongSplit * kWavesPerBlock) {
+        int lo = 0, hi = kLongScanRows - 1;      // first row whose prefix exceeds task
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (seg_end[mid] > task) hi = mid; else lo = mid + 1;
+        }
+        const int seg = task - (lo ? seg_end[lo - 1] : 0);
+        const int64_t r = row0 + lo;
+        const int32_t base = a.rowptr[r];
+        const int n = a.rowptr[r + 1] - base;
+        const int k = kept_count(a.mode, n, a.W);
+        const int t0 = seg * kTileSlots;
+        const int count = min(k - t0, kTileSlots);
+
+        RowSampler sampler;
+        sampler.init(a.mode, a.seed, r, (uint32_t)n, (uint32_t)a.W, (uint32_t)(t0 + lane), kWaveSize);
+        stage_tile(sampler, lane, kWaveSize, count, base, a.colidx, a.vals, tile);
+        wave_lds_fence();
+        P acc[CH];
+#pragma unroll
+        for (int ch = 0; ch < CH; ++ch) acc[ch].zero();
+        consume_tile<G, CH, VEC>(tile, count, e, E, a.X, a.ldx, cols, acc);
+        wave_lds_fence();
+#pragma unroll
+        for (int m = G; m < kWaveSize; m <<= 1) {
+#pragma unroll
+            for (int ch = 0; ch < CH; ++ch) acc[ch].add_xor(m);
+        }
+        if (e == 0) {
+            float* y = a.Y + r * (int64_t)a.ldy;
+#pragma unroll
+            for (int ch = 0; ch < CH; ++ch)
+                if (cols.ok[ch]) acc[ch].atomic_add(y + cols.off[ch]);
+        }
     }
 }
 
 // ---------------------------------------------------------------------------
 // Sampler export: identical team / tile schedule, sink writes CSR positions.
+// logR < 0 selects the long-row schedule instead: a whole wave per row, one
+// freshly initialised sampler per 512-slot segment.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kBlockThreads)
 es_sample_edges_kernel(const int32_t* __restrict__ rowptr, int64_t N, int32_t W, int32_t mode,
@@ -292,6 +442,8 @@ es_sample_edges_kernel(const int32_t* __restrict__ rowptr, int64_t N, int32_t W,
 {
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
+    const bool segmented = logR < 0;
+    if (segmented) logR = 0;
     const int team = kWaveSize >> logR;
     const int rs = lane >> (6 - logR);
     const int t = lane & (team - 1);
@@ -307,6 +459,8 @@ es_sample_edges_kernel(const int32_t* __restrict__ rowptr, int64_t N, int32_t W,
     int32_t* out = pos + r * (int64_t)W;
     for (int t0 = 0; t0 < k; t0 += T) {
         const int count = min(k - t0, T);
+        if (segmented)
+            sampler.init(mode, seed, r, (uint32_t)n, (uint32_t)W, (uint32_t)(t0 + t), (uint32_t)team);
         sample_tile(sampler, t, team, count,
                     [&](int slot, uint32_t entry) { out[t0 + slot] = base + (int32_t)entry; });
     }
@@ -361,13 +515,33 @@ int pick_logR(const Shape& s, double mean_kept)
 }
 
 template <int G, int CH, int VEC>
-hipError_t launch(const Args& a, dim3 grid, hipStream_t st)
+hipError_t launch(const Args& a, dim3 grid, dim3 long_grid, hipStream_t st)
 {
     hipLaunchKernelGGL((es_spmm_kernel<G, CH, VEC>), grid, dim3(kBlockThreads), 0, st, a);
-    return hipGetLastError();
+    hipError_t err = hipGetLastError();
+    if (err == hipSuccess && long_grid.x > 0) {
+        hipLaunchKernelGGL((es_spmm_long_rows_kernel<G, CH, VEC>), long_grid, dim3(kBlockThreads), 0,
+                           st, a);
+        err = hipGetLastError();
+    }
+    return err;
+}
+
+// Longest row one wave may own.  A wave retires about E*U entries per memory
+// round trip (~2 us under load) while the whole launch moves entries*(4F+8)
+// bytes at a few TB/s; the bound keeps one wave's row near 5 % of the launch.
+int32_t pick_long_k(const Shape& s, int logR, double entries, int F)
+{
+    const int U = 8 / s.CH;
+    const int E = (64 >> logR) / s.G;
+    const double k = (double)E * U * entries * (4.0 * F + 8.0) / 2.4e8;
+    if (k >= (double)(INT32_MAX - kTileSlots)) return INT32_MAX;
+    int32_t v = ((int32_t)k / kTileSlots) * kTileSlots;
+    return v < kTileSlots ? kTileSlots : v;
 }
 
 int32_t g_force_logR = -1;   // es_spmm_set_rows_per_wave override; -1 = heuristic
+int32_t g_force_long_k = 0;  // es_spmm_set_long_row_threshold override; 0 = heuristic
 
 }  // namespace
 
@@ -401,6 +575,13 @@ int es_spmm_set_rows_per_wave(int32_t rows_per_wave)
     int lg = 0;
     while ((1 << lg) < rows_per_wave) ++lg;
     g_force_logR = lg;
+    return ES_OK;
+}
+
+int es_spmm_set_long_row_threshold(int32_t entries)
+{
+    if (entries < 0) return ES_ERR_INVALID_ARG;
+    g_force_long_k = entries;
     return ES_OK;
 }
 
@@ -443,11 +624,20 @@ int es_spmm(const int32_t* rowptr, const int32_t* colidx, const float* vals, con
     a.mode = mode; a.logR = logR;
     a.nblocks = (uint32_t)nblocks; a.blocks_per_xcd = (uint32_t)per_xcd;
 
+    // rows that may keep more than long_k entries exist only in full mode or
+    // for W above the bound, and only if the matrix has that many entries
+    double entries = (double)nnz;
+    if (mode != ES_FULL && entries > (double)N * W) entries = (double)N * W;
+    a.long_k = g_force_long_k > 0 ? g_force_long_k : pick_long_k(s, logR, entries, F);
+    const bool may_be_long = nnz > a.long_k && (mode == ES_FULL || W > a.long_k);
+    const int64_t long_x = (N + kLongScanRows - 1) / kLongScanRows;
+
     const dim3 grid((uint32_t)grid_x, (uint32_t)grid_y);
+    const dim3 long_grid(may_be_long ? (uint32_t)long_x : 0u, kLongSplit, (uint32_t)grid_y);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t err = hipErrorInvalidValue;
 #define ES_CASE(G_, CH_, V_)                                   \
-    if (s.G == G_ && s.CH == CH_ && s.vec == V_) err = launch<G_, CH_, V_>(a, grid, st);
+    if (s.G == G_ && s.CH == CH_ && s.vec == V_) err = launch<G_, CH_, V_>(a, grid, long_grid, st);
     ES_CASE(4, 1, 4) ES_CASE(8, 1, 4) ES_CASE(16, 1, 4) ES_CASE(32, 1, 4)
     ES_CASE(64, 1, 4) ES_CASE(64, 2, 4) ES_CASE(64, 4, 4)
     ES_CASE(16, 1, 1) ES_CASE(32, 1, 1) ES_CASE(64, 1, 1) ES_CASE(64, 2, 1) ES_CASE(64, 4, 1)
@@ -460,7 +650,8 @@ int es_spmm_sample_edges(const int32_t* rowptr, int64_t N, int32_t W, int32_t mo
 {
     if (N < 0 || W < 1) return ES_ERR_INVALID_ARG;
     if (mode != ES_BUCKET && mode != ES_FASTRAND) return ES_ERR_INVALID_ARG;
-    if (rows_per_wave < 0 || rows_per_wave > 64 || (rows_per_wave & (rows_per_wave - 1)))
+    if (rows_per_wave < -1 || rows_per_wave > 64 ||
+        (rows_per_wave > 0 && (rows_per_wave & (rows_per_wave - 1))))
         return ES_ERR_INVALID_ARG;
     if (N == 0) return ES_OK;
     if (!rowptr || !pos || !cnt) return ES_ERR_INVALID_ARG;
@@ -471,7 +662,8 @@ int es_spmm_sample_edges(const int32_t* rowptr, int64_t N, int32_t W, int32_t mo
     const int64_t nblocks = (N + rows_per_block - 1) / rows_per_block;
     if (nblocks > INT32_MAX) return ES_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(es_sample_edges_kernel, dim3((uint32_t)nblocks), dim3(kBlockThreads), 0,
-                       static_cast<hipStream_t>(stream), rowptr, N, W, mode, seed, logR, pos, cnt);
+                       static_cast<hipStream_t>(stream), rowptr, N, W, mode, seed,
+                       rows_per_wave < 0 ? -1 : logR, pos, cnt);
     return hipGetLastError() == hipSuccess ? ES_OK : ES_ERR_LAUNCH;
 }
 
