@@ -272,6 +272,7 @@ def main() -> int:
                 log(f"  cfg{cfg} {r['mode']:8s} W={r['W']:4d}: {r['ms']:.3f} ms  {r['eff_GBps']:.0f} GB/s "
                     f"({100 * r['frac_hbm_peak']:.1f}% of peak)  cold {r['ms_cold']} ms  x{r['speedup_vs_full']} vs full")
             if cfg == 3:
+                extra.append(presampled_ablation(dw, dev))
                 extra.append(gcn_feature_sweep(dw, dev, flush))
         result["extra"] = extra
     elif not args.no_cpu_baseline:
@@ -280,6 +281,50 @@ def main() -> int:
 
     print(json.dumps(result), flush=True)
     return 0
+
+
+def _time_fn(fn, reps=10, warm=2):
+    import torch
+    for _ in range(warm):
+        fn()
+    ts = []
+    for _ in range(reps):
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        b.synchronize()
+        ts.append(a.elapsed_time(b))
+    ts.sort()
+    return ts[len(ts) // 2]
+
+
+def presampled_ablation(dw, dev):
+    """Section 5.6 of the paper: feed a pre-sampled graph to the unsampled
+    kernel and compare with the fused kernel on the original graph; here the
+    pre-sampling is es_spmm_materialize, which also gives the cost of the
+    sampling stage that the paper could not measure from inside its kernel."""
+    import torch
+    import paper_2104_10716_amd as es
+    out = {"workload": "pre-sampled graph ablation (paper Section 5.6) on the config-3 graph, F=64",
+           "rows": []}
+    for mode in ("bucket", "fastrand"):
+        for W in (64, 128, 256):
+            t_fused = _time_fn(lambda: dw.launch(mode, W))
+            orp, oci, ova = es.es_spmm_materialize(dw.rowptr, dw.colidx, dw.vals, W, mode, 0)
+            t_mat = _time_fn(lambda: es.es_spmm_materialize(dw.rowptr, dw.colidx, dw.vals, W, mode, 0,
+                                                            orp, oci, ova))
+            kept = int(orp[-1].item())
+            oci2, ova2 = oci[:kept], ova[:kept]
+            t_pre = _time_fn(lambda: es.es_spmm(orp, oci2, ova2, dw.X, dw.Y, 0, "full", F=dw.F))
+            row = {"mode": mode, "W": W, "fused_ms": round(t_fused, 4), "materialize_ms": round(t_mat, 4),
+                   "full_on_presampled_ms": round(t_pre, 4)}
+            out["rows"].append(row)
+            log(f"  ablation {mode:8s} W={W:3d}: fused {t_fused:.3f} ms | materialise {t_mat:.3f} ms + "
+                f"full SpMM on pre-sampled {t_pre:.3f} ms")
+            del orp, oci, ova
+    return out
 
 
 def gcn_feature_sweep(dw3, dev, flush):

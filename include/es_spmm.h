@@ -68,8 +68,10 @@ typedef enum {
  *   W       cap per row, >= 1 (ignored for ES_FULL).  Any W is accepted: rows
  *           longer than one LDS tile are staged tile by tile.
  *   seed    see above; ES_BUCKET and ES_FULL ignore it
- * 128-bit accesses are used when F, ldx, ldy are multiples of 4 and X, Y are
- * 16-byte aligned; any other shape takes the 32-bit kernels.
+ * X and Y must be 4-byte aligned.  Rows are read with 128-bit loads for every
+ * F >= 4; when F, ldx, ldy are multiples of 4 and X, Y are 16-byte aligned the
+ * aligned kernels run, otherwise variants that tolerate 4-byte-aligned rows
+ * (F = 41 with ldx = 41, say).
  */
 int es_spmm(const int32_t* rowptr, const int32_t* colidx, const float* vals,
             const float* X, float* Y,
@@ -91,6 +93,23 @@ int es_spmm(const int32_t* rowptr, const int32_t* colidx, const float* vals,
 int es_spmm_sample_edges(const int32_t* rowptr, int64_t N, int32_t W, int32_t mode,
                          uint64_t seed, int32_t rows_per_wave,
                          int32_t* pos, int32_t* cnt, void* stream);
+
+/*
+ * es_spmm_materialize -- write the sampled graph out as a CSR matrix of its
+ * own: the "pre-sampled graph" of Section 5.6, which the paper feeds to
+ * unsampled SpMM kernels to separate the cost of sampling from the cost of the
+ * product.  Row r of the output holds the k_r = min(n_r, W) entries es_spmm
+ * would stage, in slot order (mode ES_FULL copies the matrix).
+ *   out_rowptr [N+1] int32, written: prefix sums of k_r (out_rowptr[0] = 0)
+ *   out_colidx, out_vals: written; capacity at least min(nnz, N*W) entries
+ *   vals == NULL writes ones.  nnz: rowptr[N], a launch-shape hint as in es_spmm.
+ * es_spmm(out_rowptr, out_colidx, out_vals, ..., ES_FULL) then sums exactly the
+ * entries es_spmm(rowptr, colidx, vals, ..., W, mode, seed) sums.
+ */
+int es_spmm_materialize(const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                        int64_t N, int64_t nnz, int32_t W, int32_t mode, uint64_t seed,
+                        int32_t* out_rowptr, int32_t* out_colidx, float* out_vals,
+                        void* stream);
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* es_spmm_status_string(int status);

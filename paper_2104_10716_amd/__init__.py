@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     MODES,
     EsSpmmError,
     es_spmm,
+    es_spmm_materialize,
     es_spmm_max_W,
     es_spmm_sample_edges,
     es_spmm_set_long_row_threshold,

@@ -43,6 +43,9 @@ def load_library():
     lib.es_spmm_sample_edges.restype = ctypes.c_int
     lib.es_spmm_sample_edges.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                          ctypes.c_uint64, ctypes.c_int32, vp, vp, vp]
+    lib.es_spmm_materialize.restype = ctypes.c_int
+    lib.es_spmm_materialize.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                        ctypes.c_int32, ctypes.c_uint64, vp, vp, vp, vp]
     lib.es_spmm_status_string.restype = ctypes.c_char_p
     lib.es_spmm_status_string.argtypes = [ctypes.c_int]
     lib.es_spmm_max_W.restype = ctypes.c_int32
@@ -105,11 +108,12 @@ def es_spmm_set_long_row_threshold(entries: int) -> None:
 
 
 def es_spmm(rowptr, colidx, vals, X, Y, W: int, mode, seed: int = 0, F: Optional[int] = None,
-            stream=None):
+            stream=None, nnz: Optional[int] = None):
     """Y[:, :F] = sample_W(A) @ X[:, :F] on the tensors' device; returns Y.
     rowptr/colidx int32, vals float32 or None, X/Y 2-D float32 with unit column
     stride (row stride = leading dimension).  Enqueued on `stream` (default:
-    torch's current stream); not synchronised."""
+    torch's current stream); not synchronised.  `nnz` (default: len(colidx)) is
+    only the launch-shape hint of the C ABI."""
     import torch
     lib = load_library()
     if X.dim() != 2 or Y.dim() != 2 or X.stride(1) != 1 or Y.stride(1) != 1:
@@ -123,9 +127,10 @@ def es_spmm(rowptr, colidx, vals, X, Y, W: int, mode, seed: int = 0, F: Optional
         raise ValueError("F exceeds the width of X or Y")
     ldx = X.stride(0) if N > 1 else max(X.shape[1], 1)
     ldy = Y.stride(0) if N > 1 else max(Y.shape[1], 1)
-    nnz = colidx.numel()
-    if vals is not None and vals.numel() != nnz:
+    if vals is not None and vals.numel() != colidx.numel():
         raise ValueError("vals and colidx differ in length")
+    if nnz is None:
+        nnz = colidx.numel()
     rc = lib.es_spmm(_dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(colidx, torch.int32, "colidx"),
                      _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(X, torch.float32, "X"),
                      _dev_ptr(Y, torch.float32, "Y"), N, nnz, int(F), int(ldx), int(ldy),
@@ -154,3 +159,34 @@ def es_spmm_sample_edges(rowptr, W: int, mode, seed: int = 0, rows_per_wave: int
     if rc != 0:
         raise EsSpmmError(rc, "es_spmm_sample_edges")
     return pos, cnt
+
+
+def es_spmm_materialize(rowptr, colidx, vals, W: int, mode, seed: int = 0, out_rowptr=None,
+                        out_colidx=None, out_vals=None, stream=None):
+    """Sampled graph as CSR tensors (out_rowptr [N+1], out_colidx, out_vals).
+    The value arrays are allocated at the capacity bound min(nnz, N*W); the
+    entries in use are the first out_rowptr[-1]."""
+    import torch
+    lib = load_library()
+    N = rowptr.numel() - 1
+    nnz = colidx.numel()
+    m = _mode(mode)
+    cap = nnz if m == ES_FULL else min(nnz, N * int(W))
+    dev = rowptr.device
+    if out_rowptr is None:
+        out_rowptr = torch.empty((N + 1,), dtype=torch.int32, device=dev)
+    if out_colidx is None:
+        out_colidx = torch.empty((cap,), dtype=torch.int32, device=dev)
+    if out_vals is None:
+        out_vals = torch.empty((cap,), dtype=torch.float32, device=dev)
+    if out_rowptr.numel() != N + 1 or out_colidx.numel() < cap or out_vals.numel() < cap:
+        raise ValueError("output tensors are too small")
+    rc = lib.es_spmm_materialize(_dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(colidx, torch.int32, "colidx"),
+                                 _dev_ptr(vals, torch.float32, "vals"), N, nnz, int(W), m,
+                                 int(seed) & 0xFFFFFFFFFFFFFFFF,
+                                 _dev_ptr(out_rowptr, torch.int32, "out_rowptr"),
+                                 _dev_ptr(out_colidx, torch.int32, "out_colidx"),
+                                 _dev_ptr(out_vals, torch.float32, "out_vals"), _stream_ptr(stream))
+    if rc != 0:
+        raise EsSpmmError(rc, "es_spmm_materialize")
+    return out_rowptr, out_colidx, out_vals

@@ -130,12 +130,43 @@ __device__ __forceinline__ void wave_lds_fence()
 // ---------------------------------------------------------------------------
 // VEC-wide pieces of a row of X / Y
 // ---------------------------------------------------------------------------
-template <int VEC> struct Pack;
-template <> struct Pack<4> {
+// ALIGNED = false: rows of X / Y are only 4-byte aligned (F or a row stride is
+// not a multiple of 4).  Loads stay 128-bit (the HSA ABI runs the memory
+// pipeline in unaligned-access mode); a row's last, partial chunk is read as
+// the row's final four floats and only its components >= `first` are kept.
+typedef float float4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+
+template <int VEC, bool ALIGNED> struct Pack;
+template <bool ALIGNED> struct Pack<4, ALIGNED> {
     float4 v;
     __device__ __forceinline__ void zero() { v = make_float4(0.f, 0.f, 0.f, 0.f); }
-    __device__ __forceinline__ void load(const float* p) { v = *reinterpret_cast<const float4*>(p); }
-    __device__ __forceinline__ void store(float* p) const { *reinterpret_cast<float4*>(p) = v; }
+    __device__ __forceinline__ void load(const float* p)
+    {
+        if (ALIGNED) {
+            v = *reinterpret_cast<const float4*>(p);
+        } else {
+            const float4_a4 t = *reinterpret_cast<const float4_a4*>(p);
+            v = make_float4(t.x, t.y, t.z, t.w);
+        }
+    }
+    __device__ __forceinline__ void store(float* p, int first) const
+    {
+        if (ALIGNED) {
+            *reinterpret_cast<float4*>(p) = v;
+        } else {
+            if (first <= 0) p[0] = v.x;
+            if (first <= 1) p[1] = v.y;
+            if (first <= 2) p[2] = v.z;
+            p[3] = v.w;
+        }
+    }
+    __device__ __forceinline__ void atomic_add(float* p, int first) const
+    {
+        if (first <= 0) unsafeAtomicAdd(p, v.x);
+        if (first <= 1) unsafeAtomicAdd(p + 1, v.y);
+        if (first <= 2) unsafeAtomicAdd(p + 2, v.z);
+        unsafeAtomicAdd(p + 3, v.w);
+    }
     __device__ __forceinline__ void fma(float a, const Pack& x)
     {
         v.x = fmaf(a, x.v.x, v.x); v.y = fmaf(a, x.v.y, v.y);
@@ -146,29 +177,27 @@ template <> struct Pack<4> {
         v.x += __shfl_xor(v.x, mask, kWaveSize); v.y += __shfl_xor(v.y, mask, kWaveSize);
         v.z += __shfl_xor(v.z, mask, kWaveSize); v.w += __shfl_xor(v.w, mask, kWaveSize);
     }
-    __device__ __forceinline__ void atomic_add(float* p) const
-    {
-        unsafeAtomicAdd(p, v.x); unsafeAtomicAdd(p + 1, v.y);
-        unsafeAtomicAdd(p + 2, v.z); unsafeAtomicAdd(p + 3, v.w);
-    }
 };
-template <> struct Pack<1> {
+template <bool ALIGNED> struct Pack<1, ALIGNED> {
     float v;
     __device__ __forceinline__ void zero() { v = 0.f; }
     __device__ __forceinline__ void load(const float* p) { v = *p; }
-    __device__ __forceinline__ void store(float* p) const { *p = v; }
+    __device__ __forceinline__ void store(float* p, int) const { *p = v; }
+    __device__ __forceinline__ void atomic_add(float* p, int) const { unsafeAtomicAdd(p, v); }
     __device__ __forceinline__ void fma(float a, const Pack& x) { v = fmaf(a, x.v, v); }
     __device__ __forceinline__ void add_xor(int mask) { v += __shfl_xor(v, mask, kWaveSize); }
-    __device__ __forceinline__ void atomic_add(float* p) const { unsafeAtomicAdd(p, v); }
 };
 
 constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v >> 1); }
 
 // Feature columns one lane covers: CH chunks of VEC floats, chunk ch at column
-// colblk + (ch*G + l)*VEC.  Lanes past F re-read column 0 and never store.
-template <int G, int CH, int VEC>
+// colblk + (ch*G + l)*VEC.  Lanes past F re-read column 0 and never store.  In
+// the unaligned variant a chunk that straddles F is moved back to end at F and
+// `first` marks its first component that belongs to this lane.
+template <int G, int CH, int VEC, bool ALIGNED>
 struct LaneCols {
     int off[CH];
+    int first[CH];
     bool ok[CH];
     __device__ __forceinline__ void init(int colblk, int l, int F)
     {
@@ -177,6 +206,11 @@ struct LaneCols {
             const int c = colblk + (ch * G + l) * VEC;
             ok[ch] = c < F;
             off[ch] = ok[ch] ? c : 0;
+            first[ch] = 0;
+            if (!ALIGNED && VEC > 1 && ok[ch] && c + VEC > F) {
+                off[ch] = F - VEC;
+                first[ch] = c - off[ch];
+            }
         }
     }
 };
@@ -198,13 +232,14 @@ __device__ __forceinline__ void stage_tile(RowSampler& sampler, int t, int team,
 // Stage 2 of Algorithm 1 for one tile: this lane's edge slot e (of E) walks
 // tile entries e, e+E, ... < count, U at a time: U LDS broadcasts, then U*CH
 // independent loads of X, then the FMAs.
-template <int G, int CH, int VEC>
+template <int G, int CH, int VEC, bool ALIGNED>
 __device__ __forceinline__ void consume_tile(const uint2* tile, int count, int e, int E,
                                              const float* __restrict__ X, int64_t ldx,
-                                             const LaneCols<G, CH, VEC>& cols, Pack<VEC> (&acc)[CH])
+                                             const LaneCols<G, CH, VEC, ALIGNED>& cols,
+                                             Pack<VEC, ALIGNED> (&acc)[CH])
 {
     constexpr int U = 8 / CH;
-    using P = Pack<VEC>;
+    using P = Pack<VEC, ALIGNED>;
     int j = e;
     for (; j + (U - 1) * E < count; j += U * E) {            // full batches
         uint2 ed[U];
@@ -260,11 +295,11 @@ __device__ __forceinline__ int kept_count(int mode, int n, int W)
 // Fused kernel (Algorithm 1).  G lanes x CH chunks x VEC floats cover one block
 // of G*CH*VEC feature columns (blockIdx.y selects the block).
 // ---------------------------------------------------------------------------
-template <int G, int CH, int VEC>
+template <int G, int CH, int VEC, bool ALIGNED>
 __global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
 {
     constexpr int LOG_G = ilog2(G);
-    using P = Pack<VEC>;
+    using P = Pack<VEC, ALIGNED>;
 
     __shared__ uint2 lds[kWavesPerBlock * kWaveTileStride];
 
@@ -296,7 +331,7 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
     int k = kept_count(a.mode, n, a.W);
     if (k > a.long_k) k = 0;                     // long-row kernel adds this row; store zeros here
 
-    LaneCols<G, CH, VEC> cols;
+    LaneCols<G, CH, VEC, ALIGNED> cols;
     cols.init(blockIdx.y * (G * CH * VEC), l, a.F);
 
     RowSampler sampler;
@@ -310,7 +345,7 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
         const int count = min(k - t0, T);
         stage_tile(sampler, t, team, count, base, a.colidx, a.vals, tile);
         wave_lds_fence();
-        consume_tile<G, CH, VEC>(tile, count, e, E, a.X, a.ldx, cols, acc);
+        consume_tile<G, CH, VEC, ALIGNED>(tile, count, e, E, a.X, a.ldx, cols, acc);
         wave_lds_fence();
     }
 
@@ -323,7 +358,7 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
         float* y = a.Y + r * (int64_t)a.ldy;
 #pragma unroll
         for (int ch = 0; ch < CH; ++ch)
-            if (cols.ok[ch]) acc[ch].store(y + cols.off[ch]);
+            if (cols.ok[ch]) acc[ch].store(y + cols.off[ch], cols.first[ch]);
     }
 }
 
@@ -335,12 +370,12 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
 // the row; its partial sums are added to Y (zeroed by the row kernel) with
 // fp32 atomics, so the summation order across segments is not fixed.
 // ---------------------------------------------------------------------------
-template <int G, int CH, int VEC>
+template <int G, int CH, int VEC, bool ALIGNED>
 __global__ void __launch_bounds__(kBlockThreads) es_spmm_long_rows_kernel(const Args a)
 {
     constexpr int LOG_G = ilog2(G);
     constexpr int kRowsPerThread = kLongScanRows / kBlockThreads;
-    using P = Pack<VEC>;
+    using P = Pack<VEC, ALIGNED>;
 
     __shared__ uint2 lds[kWavesPerBlock * kWaveTileStride];
     __shared__ int seg_end[kLongScanRows];       // inclusive prefix sum of segment counts
@@ -389,7 +424,7 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_long_rows_kernel(const 
     const int l = lane & (G - 1);
     constexpr int E = kWaveSize / G;
     uint2* tile = lds + wave * kWaveTileStride;
-    LaneCols<G, CH, VEC> cols;
+    LaneCols<G, CH, VEC, ALIGNED> cols;
     cols.init(blockIdx.z * (G * CH * VEC), l, a.F);
 
     const int gw = blockIdx.y * kWavesPerBlock + wave;
@@ -414,7 +449,7 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_long_rows_kernel(const 
         P acc[CH];
 #pragma unroll
         for (int ch = 0; ch < CH; ++ch) acc[ch].zero();
-        consume_tile<G, CH, VEC>(tile, count, e, E, a.X, a.ldx, cols, acc);
+        consume_tile<G, CH, VEC, ALIGNED>(tile, count, e, E, a.X, a.ldx, cols, acc);
         wave_lds_fence();
 #pragma unroll
         for (int m = G; m < kWaveSize; m <<= 1) {
@@ -425,7 +460,7 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_long_rows_kernel(const 
             float* y = a.Y + r * (int64_t)a.ldy;
 #pragma unroll
             for (int ch = 0; ch < CH; ++ch)
-                if (cols.ok[ch]) acc[ch].atomic_add(y + cols.off[ch]);
+                if (cols.ok[ch]) acc[ch].atomic_add(y + cols.off[ch], cols.first[ch]);
         }
     }
 }
@@ -469,10 +504,132 @@ es_sample_edges_kernel(const int32_t* __restrict__ rowptr, int64_t N, int32_t W,
 }
 
 // ---------------------------------------------------------------------------
+// Materialised sampled graph (the pre-sampled input of Section 5.6): row
+// pointers of the kept counts by a three-step in-place scan, then the sampled
+// (column, value) pairs in slot order.
+// ---------------------------------------------------------------------------
+constexpr int kScanRows = 1024;                       // rows per scan workgroup
+constexpr int kScanPerThread = kScanRows / kBlockThreads;
+
+// Step 1: out[r+1] = inclusive prefix of k inside the row's 1024-row block.
+__global__ void __launch_bounds__(kBlockThreads)
+es_kept_scan_local_kernel(const int32_t* __restrict__ rowptr, int64_t N, int32_t W, int32_t mode,
+                          int32_t* __restrict__ out)
+{
+    __shared__ int wave_total[kWavesPerBlock];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWaveSize - 1);
+    const int wave = tid >> 6;
+    const int64_t r0 = (int64_t)blockIdx.x * kScanRows + tid * kScanPerThread;
+    int k[kScanPerThread];
+    int mine = 0;
+#pragma unroll
+    for (int i = 0; i < kScanPerThread; ++i) {
+        const int64_t r = r0 + i;
+        k[i] = (r < N) ? kept_count(mode, rowptr[r + 1] - rowptr[r], W) : 0;
+        mine += k[i];
+    }
+    int incl = mine;
+#pragma unroll
+    for (int d = 1; d < kWaveSize; d <<= 1) {
+        const int up = __shfl_up(incl, d, kWaveSize);
+        if (lane >= d) incl += up;
+    }
+    if (lane == kWaveSize - 1) wave_total[wave] = incl;
+    __syncthreads();
+    int run = incl - mine;
+    for (int w = 0; w < wave; ++w) run += wave_total[w];
+#pragma unroll
+    for (int i = 0; i < kScanPerThread; ++i) {
+        run += k[i];
+        if (r0 + i < N) out[r0 + i + 1] = run;
+    }
+    if (blockIdx.x == 0 && tid == 0) out[0] = 0;
+}
+
+// Step 2 (one workgroup): turn the block totals, stored at each block's last
+// row, into global inclusive prefixes.
+__global__ void __launch_bounds__(kBlockThreads)
+es_kept_scan_blocks_kernel(int64_t N, int32_t* __restrict__ out)
+{
+    __shared__ int wave_total[kWavesPerBlock];
+    __shared__ int carry_s;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWaveSize - 1);
+    const int wave = tid >> 6;
+    const int64_t nblocks = (N + kScanRows - 1) / kScanRows;
+    if (tid == 0) carry_s = 0;
+    __syncthreads();
+    for (int64_t b0 = 0; b0 < nblocks; b0 += kBlockThreads) {
+        const int64_t b = b0 + tid;
+        const int64_t last = min((b + 1) * (int64_t)kScanRows, N);   // index of the block's total
+        const int v = (b < nblocks) ? out[last] : 0;
+        int incl = v;
+#pragma unroll
+        for (int d = 1; d < kWaveSize; d <<= 1) {
+            const int up = __shfl_up(incl, d, kWaveSize);
+            if (lane >= d) incl += up;
+        }
+        if (lane == kWaveSize - 1) wave_total[wave] = incl;
+        __syncthreads();
+        int run = incl + carry_s;
+        for (int w = 0; w < wave; ++w) run += wave_total[w];
+        if (b < nblocks) out[last] = run;
+        __syncthreads();
+        if (tid == kBlockThreads - 1) carry_s = run;
+        __syncthreads();
+    }
+}
+
+// Step 3: add the previous block's global prefix to every entry of a block
+// except its last (already global).
+__global__ void __launch_bounds__(kBlockThreads)
+es_kept_scan_add_kernel(int64_t N, int32_t* __restrict__ out)
+{
+    const int64_t b = blockIdx.x + 1;                 // block 0 needs no offset
+    const int offset = out[b * kScanRows];
+    const int64_t last = min((b + 1) * (int64_t)kScanRows, N);
+    for (int64_t i = b * kScanRows + 1 + threadIdx.x; i < last; i += kBlockThreads) out[i] += offset;
+}
+
+// One team of 64/R lanes per row, same sampler walk as stage 1 of the fused kernel.
+__global__ void __launch_bounds__(kBlockThreads)
+es_materialize_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+                      const float* __restrict__ vals, int64_t N, int32_t W, int32_t mode,
+                      uint64_t seed, int32_t logR, const int32_t* __restrict__ out_rowptr,
+                      int32_t* __restrict__ out_colidx, float* __restrict__ out_vals)
+{
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = threadIdx.x >> 6;
+    const int team = kWaveSize >> logR;
+    const int rs = lane >> (6 - logR);
+    const int t = lane & (team - 1);
+    const int T = kTileSlots >> logR;
+    const int64_t r = ((((int64_t)blockIdx.x * kWavesPerBlock) + wave) << logR) + rs;
+    if (r >= N) return;
+    const int32_t base = rowptr[r];
+    const int32_t n = rowptr[r + 1] - base;
+    const int k = kept_count(mode, n, W);
+    const int64_t obase = out_rowptr[r];
+
+    RowSampler sampler;
+    sampler.init(mode, seed, r, (uint32_t)n, (uint32_t)W, (uint32_t)t, (uint32_t)team);
+    for (int t0 = 0; t0 < k; t0 += T) {
+        const int count = min(k - t0, T);
+        sample_tile(sampler, t, team, count, [&](int slot, uint32_t entry) {
+            const int64_t p = (int64_t)base + entry;
+            out_colidx[obase + t0 + slot] = colidx[p];
+            out_vals[obase + t0 + slot] = vals ? vals[p] : 1.0f;
+        });
+    }
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 struct Shape {
     int vec, G, CH;
+    bool aligned;
 };
 
 int next_pow2(int v)
@@ -482,15 +639,16 @@ int next_pow2(int v)
     return p;
 }
 
-// Lanes x chunks that cover F columns with VEC-wide accesses.
-Shape pick_shape(int F, bool vec4)
+// Lanes x chunks that cover F columns: 128-bit accesses whenever F >= 4
+// (aligned or not), 32-bit ones for F < 4.
+Shape pick_shape(int F, bool aligned)
 {
     Shape s;
-    s.vec = vec4 ? 4 : 1;
+    s.aligned = aligned;
+    s.vec = (aligned || F >= 4) ? 4 : 1;
     const int q = (F + s.vec - 1) / s.vec;                 // accesses per row
-    const int gmin = vec4 ? 4 : 16;
     s.G = next_pow2(q);
-    if (s.G < gmin) s.G = gmin;
+    if (s.G < 4) s.G = 4;
     s.CH = 1;
     if (s.G > 64) {
         s.G = 64;
@@ -514,14 +672,14 @@ int pick_logR(const Shape& s, double mean_kept)
     return logR;
 }
 
-template <int G, int CH, int VEC>
+template <int G, int CH, int VEC, bool ALIGNED>
 hipError_t launch(const Args& a, dim3 grid, dim3 long_grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((es_spmm_kernel<G, CH, VEC>), grid, dim3(kBlockThreads), 0, st, a);
+    hipLaunchKernelGGL((es_spmm_kernel<G, CH, VEC, ALIGNED>), grid, dim3(kBlockThreads), 0, st, a);
     hipError_t err = hipGetLastError();
     if (err == hipSuccess && long_grid.x > 0) {
-        hipLaunchKernelGGL((es_spmm_long_rows_kernel<G, CH, VEC>), long_grid, dim3(kBlockThreads), 0,
-                           st, a);
+        hipLaunchKernelGGL((es_spmm_long_rows_kernel<G, CH, VEC, ALIGNED>), long_grid,
+                           dim3(kBlockThreads), 0, st, a);
         err = hipGetLastError();
     }
     return err;
@@ -596,10 +754,12 @@ int es_spmm(const int32_t* rowptr, const int32_t* colidx, const float* vals, con
     if (!rowptr || !X || !Y) return ES_ERR_INVALID_ARG;
     if (nnz > 0 && !colidx) return ES_ERR_INVALID_ARG;
 
-    const bool vec4 = (F % 4 == 0) && (ldx % 4 == 0) && (ldy % 4 == 0) &&
-                      (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
-                      (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
-    const Shape s = pick_shape(F, vec4);
+    const bool aligned = (F % 4 == 0) && (ldx % 4 == 0) && (ldy % 4 == 0) &&
+                         (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
+                         (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
+    if (reinterpret_cast<uintptr_t>(X) % 4 || reinterpret_cast<uintptr_t>(Y) % 4)
+        return ES_ERR_INVALID_ARG;
+    const Shape s = pick_shape(F, aligned);
 
     double mean = (double)nnz / (double)N;
     if (mode != ES_FULL && mean > (double)W) mean = (double)W;
@@ -625,24 +785,65 @@ int es_spmm(const int32_t* rowptr, const int32_t* colidx, const float* vals, con
     a.nblocks = (uint32_t)nblocks; a.blocks_per_xcd = (uint32_t)per_xcd;
 
     // rows that may keep more than long_k entries exist only in full mode or
-    // for W above the bound, and only if the matrix has that many entries
+    // for W above the bound (nnz is a hint, so it does not gate the launch)
     double entries = (double)nnz;
     if (mode != ES_FULL && entries > (double)N * W) entries = (double)N * W;
     a.long_k = g_force_long_k > 0 ? g_force_long_k : pick_long_k(s, logR, entries, F);
-    const bool may_be_long = nnz > a.long_k && (mode == ES_FULL || W > a.long_k);
+    const bool may_be_long = mode == ES_FULL || W > a.long_k;
     const int64_t long_x = (N + kLongScanRows - 1) / kLongScanRows;
 
     const dim3 grid((uint32_t)grid_x, (uint32_t)grid_y);
     const dim3 long_grid(may_be_long ? (uint32_t)long_x : 0u, kLongSplit, (uint32_t)grid_y);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t err = hipErrorInvalidValue;
-#define ES_CASE(G_, CH_, V_)                                   \
-    if (s.G == G_ && s.CH == CH_ && s.vec == V_) err = launch<G_, CH_, V_>(a, grid, long_grid, st);
-    ES_CASE(4, 1, 4) ES_CASE(8, 1, 4) ES_CASE(16, 1, 4) ES_CASE(32, 1, 4)
-    ES_CASE(64, 1, 4) ES_CASE(64, 2, 4) ES_CASE(64, 4, 4)
-    ES_CASE(16, 1, 1) ES_CASE(32, 1, 1) ES_CASE(64, 1, 1) ES_CASE(64, 2, 1) ES_CASE(64, 4, 1)
+#define ES_CASE(G_, CH_, V_, A_)                                                   \
+    if (s.G == G_ && s.CH == CH_ && s.vec == V_ && s.aligned == A_)                \
+        err = launch<G_, CH_, V_, A_>(a, grid, long_grid, st);
+    ES_CASE(4, 1, 4, true) ES_CASE(8, 1, 4, true) ES_CASE(16, 1, 4, true) ES_CASE(32, 1, 4, true)
+    ES_CASE(64, 1, 4, true) ES_CASE(64, 2, 4, true) ES_CASE(64, 4, 4, true)
+    ES_CASE(4, 1, 4, false) ES_CASE(8, 1, 4, false) ES_CASE(16, 1, 4, false) ES_CASE(32, 1, 4, false)
+    ES_CASE(64, 1, 4, false) ES_CASE(64, 2, 4, false) ES_CASE(64, 4, 4, false)
+    ES_CASE(4, 1, 1, false)
 #undef ES_CASE
     return err == hipSuccess ? ES_OK : ES_ERR_LAUNCH;
+}
+
+int es_spmm_materialize(const int32_t* rowptr, const int32_t* colidx, const float* vals, int64_t N,
+                        int64_t nnz, int32_t W, int32_t mode, uint64_t seed, int32_t* out_rowptr,
+                        int32_t* out_colidx, float* out_vals, void* stream)
+{
+    if (N < 0 || nnz < 0 || nnz > INT32_MAX) return ES_ERR_INVALID_ARG;
+    if (mode != ES_FULL && mode != ES_BUCKET && mode != ES_FASTRAND) return ES_ERR_INVALID_ARG;
+    if (mode != ES_FULL && W < 1) return ES_ERR_INVALID_ARG;
+    if (!out_rowptr) return ES_ERR_INVALID_ARG;
+    if (N > 0 && (!rowptr || !out_colidx || !out_vals)) return ES_ERR_INVALID_ARG;
+    if (nnz > 0 && !colidx) return ES_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int32_t Wk = (mode == ES_FULL) ? INT32_MAX : W;
+    const int64_t nscan = N == 0 ? 1 : (N + kScanRows - 1) / kScanRows;
+    if (nscan > INT32_MAX) return ES_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(es_kept_scan_local_kernel, dim3((uint32_t)nscan), dim3(kBlockThreads), 0, st,
+                       rowptr, N, Wk, mode, out_rowptr);
+    if (hipGetLastError() != hipSuccess) return ES_ERR_LAUNCH;
+    if (N == 0) return ES_OK;
+    if (nscan > 1) {
+        hipLaunchKernelGGL(es_kept_scan_blocks_kernel, dim3(1), dim3(kBlockThreads), 0, st, N, out_rowptr);
+        if (hipGetLastError() != hipSuccess) return ES_ERR_LAUNCH;
+        hipLaunchKernelGGL(es_kept_scan_add_kernel, dim3((uint32_t)(nscan - 1)), dim3(kBlockThreads), 0,
+                           st, N, out_rowptr);
+        if (hipGetLastError() != hipSuccess) return ES_ERR_LAUNCH;
+    }
+    // lanes per row: about one per kept entry of a typical row
+    double mean = (double)nnz / (double)N;
+    if (mean > (double)Wk) mean = (double)Wk;
+    int logR = 6;
+    while (logR > 0 && (double)(kWaveSize >> logR) < mean) --logR;
+    const int64_t rows_per_block = (int64_t)kWavesPerBlock << logR;
+    const int64_t nblocks = (N + rows_per_block - 1) / rows_per_block;
+    if (nblocks > INT32_MAX) return ES_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(es_materialize_kernel, dim3((uint32_t)nblocks), dim3(kBlockThreads), 0, st,
+                       rowptr, colidx, vals, N, Wk, mode, seed, logR, out_rowptr, out_colidx, out_vals);
+    return hipGetLastError() == hipSuccess ? ES_OK : ES_ERR_LAUNCH;
 }
 
 int es_spmm_sample_edges(const int32_t* rowptr, int64_t N, int32_t W, int32_t mode, uint64_t seed,

@@ -138,6 +138,20 @@ def test_degenerate_inputs(es):
     du = DeviceCSR(rowptr, colidx, None, X)
     for mode, W in (("full", 0), ("bucket", 2), ("fastrand", 2)):
         check_against_oracle(du, W, mode, 5, what=f"unit values {mode}")
+    # the nnz argument is only a launch-shape hint: any value gives the same result
+    import paper_2104_10716_amd as esm
+    rowptr, colidx, vals, X = _random_graph(400, 40.0, seed=8, F=32)
+    dh = DeviceCSR(rowptr, colidx, vals, X)
+    esm.es_spmm_set_long_row_threshold(16)
+    for mode, W in (("full", 0), ("fastrand", 6), ("fastrand", 30)):
+        ref = dh.run(W, mode, 3)
+        for hint in (0, 1, 10 ** 9):
+            Y = torch.empty_like(ref)
+            esm.es_spmm(dh.rowptr, dh.colidx, dh.vals, dh.X, Y, W, mode, 3, nnz=hint)
+            torch.cuda.synchronize()
+            assert torch.allclose(Y, ref, rtol=1e-4, atol=1e-5), (mode, hint)
+        check_against_oracle(dh, W, mode, 3, what=f"nnz hint {mode}")
+    esm.es_spmm_set_long_row_threshold(0)
     # N == 0 is a no-op
     e = torch.empty((0, 4), dtype=torch.float32, device="cuda:0")
     es.es_spmm(torch.zeros(1, dtype=torch.int32, device="cuda:0"),
@@ -177,6 +191,68 @@ def test_determinism_across_launches(es):
     assert torch.equal(p1, p2) and torch.equal(c1, c2)
     p0, _ = d.edges(32, "fastrand", 0)
     assert not torch.equal(p0, p1)
+
+
+def _oracle_sampled_csr(rowptr, colidx, vals, W, mode, seed):
+    """Sampled graph as CSR, built on the host from the oracle's kept lists."""
+    import oracle
+    pos, cnt = oracle.kept(rowptr, W, mode, seed)
+    out_rowptr = np.zeros(rowptr.shape[0], dtype=np.int64)
+    out_rowptr[1:] = np.cumsum(cnt)
+    if pos.shape[1]:
+        keep = pos[pos >= 0]                       # row-major: row by row, slot order
+    else:
+        keep = np.zeros(0, dtype=np.int32)
+    v = np.ones(keep.size, dtype=np.float32) if vals is None else vals[keep]
+    return out_rowptr.astype(np.int32), colidx[keep], v
+
+
+@pytest.mark.parametrize("n,avg", [(1, 3.0), (700, 9.0), (5000, 30.0)])
+def test_materialized_sampled_graph(es, n, avg):
+    """es_spmm_materialize (pre-sampled graph of Section 5.6): the CSR it writes
+    equals the oracle's kept lists bit for bit, and the full product on it
+    equals the fused sampled product."""
+    import torch
+    from gpu_util import DeviceCSR, check_Y
+    import oracle
+    rowptr, colidx, vals, X = _random_graph(n, avg, seed=n, F=24, empty_frac=0.2 if n > 1 else 0.0)
+    d = DeviceCSR(rowptr, colidx, vals, X)
+    maxdeg = max(1, int(np.diff(rowptr).max()))
+    for mode in ("bucket", "fastrand", "full"):
+        for W in (1, 5, maxdeg + 1):
+            for seed in (0, 99):
+                orp, oci, ova = es.es_spmm_materialize(d.rowptr, d.colidx, d.vals, W, mode, seed)
+                torch.cuda.synchronize()
+                erp, eci, eva = _oracle_sampled_csr(rowptr, colidx, vals, W, mode, seed)
+                kept = int(erp[-1])
+                assert np.array_equal(orp.cpu().numpy(), erp), (mode, W, seed)
+                assert np.array_equal(oci.cpu().numpy()[:kept], eci), (mode, W, seed)
+                assert np.array_equal(ova.cpu().numpy()[:kept], eva), (mode, W, seed)
+                Y = torch.full((d.N, d.F), float("nan"), dtype=torch.float32, device="cuda:0")
+                es.es_spmm(orp, oci[:kept], ova[:kept], d.X, Y, 0, "full")
+                torch.cuda.synchronize()
+                Yref, den = oracle.spmm(rowptr, colidx, vals, X, d.F, W, mode, seed)
+                check_Y(Y.cpu().numpy(), Yref, den, f"full product on materialised {mode} W={W}")
+    # unweighted input writes ones
+    orp, oci, ova = es.es_spmm_materialize(d.rowptr, d.colidx, None, 3, "fastrand", 1)
+    torch.cuda.synchronize()
+    assert (ova.cpu().numpy()[:int(orp[-1])] == 1.0).all()
+
+
+def test_materialized_row_pointers_many_blocks(es):
+    """Row-pointer scan across many 1024-row blocks (config 2, 170 k rows)."""
+    import torch
+    w = _workload(2)
+    from gpu_util import DeviceCSR
+    d = DeviceCSR(w.rowptr, w.colidx, w.vals, w.X)
+    for mode, W in (("fastrand", 16), ("bucket", 128), ("full", 0)):
+        orp, oci, ova = es.es_spmm_materialize(d.rowptr, d.colidx, d.vals, W, mode, 0)
+        torch.cuda.synchronize()
+        erp, eci, eva = _oracle_sampled_csr(w.rowptr, w.colidx, w.vals, W, mode, 0)
+        kept = int(erp[-1])
+        assert np.array_equal(orp.cpu().numpy(), erp)
+        assert np.array_equal(oci.cpu().numpy()[:kept], eci)
+        assert np.array_equal(ova.cpu().numpy()[:kept], eva)
 
 
 # --------------------------------------------------------------------------
@@ -235,6 +311,12 @@ def test_config3_social_like_full_size(es):
         for mode in ("bucket", "fastrand"):
             check_edges(d, W, mode, 0)
             _say(f"cfg3 {mode} W={W}: edge lists identical")
+    # the widths the paper needs for Bucket on its densest graph (S = 1792, 2304):
+    # several LDS tiles per row, and rows above the long-row threshold
+    for W in (1792, 2304):
+        for mode in ("bucket", "fastrand"):
+            worst = check_against_oracle(d, W, mode, 0, rows=rows, what=f"cfg3 {mode} W={W}")
+            _say(f"cfg3 {mode} W={W}: max normalised error {worst:.2e}")
 
 
 def test_config5_feature_sweep_on_config3_graph(es):
