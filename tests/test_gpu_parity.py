@@ -168,6 +168,48 @@ def test_degenerate_inputs(es):
     assert torch.equal(Y, du.run(2, "fastrand", 5))
 
 
+def test_hip_graph_capture_and_replay(es):
+    """es_spmm only enqueues kernels, so a caller can capture it in a HIP graph.
+    Replays (with eager work and synchronisations in between) must reproduce the
+    eager result every time, also after the inputs change in place."""
+    import torch
+    from gpu_util import DeviceCSR, check_against_oracle
+    rowptr, colidx, vals, X = _random_graph(3000, 20.0, seed=21, F=64)
+    d = DeviceCSR(rowptr, colidx, vals, X)
+    es.es_spmm_set_long_row_threshold(24)          # full mode then uses both kernels
+    Yf = torch.zeros((d.N, d.F), dtype=torch.float32, device="cuda:0")
+    Ys = torch.zeros_like(Yf)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(2):                         # warm-up outside capture
+            es.es_spmm(d.rowptr, d.colidx, d.vals, d.X, Yf, 0, "full")
+            es.es_spmm(d.rowptr, d.colidx, d.vals, d.X, Ys, 8, "fastrand", 5)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        es.es_spmm(d.rowptr, d.colidx, d.vals, d.X, Yf, 0, "full")
+        es.es_spmm(d.rowptr, d.colidx, d.vals, d.X, Ys, 8, "fastrand", 5)
+    for rep in range(4):
+        Yf.fill_(float("nan"))
+        Ys.fill_(float("nan"))
+        if rep == 2:
+            d.X.mul_(-0.5)                          # new input values, same buffers
+            d.h_X = d.h_X * np.float32(-0.5)
+        g.replay()
+        torch.cuda.synchronize()
+        eager_s = d.run(8, "fastrand", 5)
+        assert torch.equal(Ys, eager_s), f"replay {rep}: sampled result differs from eager"
+        eager_f = d.run(0, "full")
+        assert torch.allclose(Yf, eager_f, rtol=1e-4, atol=1e-5), f"replay {rep}: full result differs"
+        import oracle
+        Yref, den = oracle.spmm(rowptr, colidx, vals, d.h_X, d.F, 8, "fastrand", 5)
+        from gpu_util import check_Y
+        check_Y(Ys.cpu().numpy(), Yref, den, f"graph replay {rep}")
+    es.es_spmm_set_long_row_threshold(0)
+
+
 def test_determinism_across_launches(es):
     """Same inputs, same launch shape: bit-identical Y and edge lists (the
     sampler is static for a given seed, Section 6.2).  Full mode is
@@ -317,6 +359,48 @@ def test_config3_social_like_full_size(es):
         for mode in ("bucket", "fastrand"):
             worst = check_against_oracle(d, W, mode, 0, rows=rows, what=f"cfg3 {mode} W={W}")
             _say(f"cfg3 {mode} W={W}: max normalised error {worst:.2e}")
+
+
+@pytest.mark.parametrize("cfg", [3, 4])
+def test_full_size_every_row_counts_its_kept_entries(es, cfg):
+    """A property that holds at any size and covers EVERY row of the big
+    graphs: with unit values and X = 1 each output equals the number of kept
+    entries min(deg, W) (Section 4.2), exactly -- small integers are exact in
+    fp32 whatever the summation order."""
+    import torch
+    w = _workload(cfg)
+    dev = "cuda:0"
+    rowptr = torch.from_numpy(w.rowptr).to(dev)
+    colidx = torch.from_numpy(w.colidx).to(dev)
+    F = 8
+    X = torch.ones((w.N, F), dtype=torch.float32, device=dev)
+    Y = torch.empty((w.N, F), dtype=torch.float32, device=dev)
+    deg = torch.from_numpy(np.diff(w.rowptr).astype(np.float32)).to(dev)
+    for mode, W in (("full", 0), ("bucket", 16), ("fastrand", 16), ("fastrand", 256), ("bucket", 2304)):
+        Y.fill_(float("nan"))
+        es.es_spmm(rowptr, colidx, None, X, Y, W, mode, 0)
+        torch.cuda.synchronize()
+        expect = deg if mode == "full" else torch.clamp(deg, max=float(W))
+        assert torch.equal(Y, expect[:, None].expand(-1, F)), f"cfg{cfg} {mode} W={W}"
+        _say(f"cfg{cfg} {mode} W={W}: all {w.N} rows count their kept entries exactly")
+    # X[j] = j (exact in fp32 below 2^24) with a single column: FastRand must
+    # pick exactly the oracle's columns; compare the exact integer sums of the
+    # column ids on every row whose sum stays below 2^24
+    if w.N < 2 ** 24:
+        import oracle
+        Xid = torch.arange(w.N, dtype=torch.float32, device=dev).reshape(-1, 1).repeat(1, 4).contiguous()
+        Y4 = torch.empty((w.N, 4), dtype=torch.float32, device=dev)
+        W = 4
+        es.es_spmm(rowptr, colidx, None, Xid, Y4, W, "fastrand", 0)
+        torch.cuda.synchronize()
+        pos, cnt = oracle.kept(w.rowptr, W, "fastrand", 0)
+        cols = np.where(pos >= 0, w.colidx[np.maximum(pos, 0)], 0).astype(np.int64)
+        sums = cols.sum(axis=1)
+        ok = sums < 2 ** 24
+        # partial sums of non-negative integers below 2^24 are exact in any order
+        got = Y4[:, 0].cpu().numpy().astype(np.int64)
+        assert np.array_equal(got[ok], sums[ok]), f"cfg{cfg}: column-id sums differ"
+        _say(f"cfg{cfg} fastrand W=4: column-id sums exact on {int(ok.sum())} of {w.N} rows")
 
 
 def test_config5_feature_sweep_on_config3_graph(es):
