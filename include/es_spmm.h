@@ -32,6 +32,17 @@ extern "C" {
 /* Sampling strategy (Section 4.4).  FULL keeps every entry: the exact product. */
 typedef enum { ES_FULL = 0, ES_BUCKET = 1, ES_FASTRAND = 2 } es_mode_t;
 
+/* Row normalisation folded into the kernel (Section 6.1: sampling changes a
+ * row's edge count, so the degree normalisation cannot stay outside the SpMM).
+ * The row's sum is multiplied by a factor of its stored count n and its kept
+ * count k; rows with k == 0 stay zero. */
+typedef enum {
+    ES_NORM_NONE = 0,     /* 1                                                     */
+    ES_NORM_MEAN = 1,     /* 1 / k        mean over the kept neighbours            */
+    ES_NORM_RSQRT = 2,    /* 1 / sqrt(k)  destination side of the symmetric norm   */
+    ES_NORM_RESCALE = 3   /* n / k        estimate of the full row sum             */
+} es_norm_t;
+
 typedef enum {
     ES_OK = 0,
     ES_ERR_INVALID_ARG = -1,  /* null pointer, negative size, ld < F, W < 1, bad mode */
@@ -77,6 +88,18 @@ int es_spmm(const int32_t* rowptr, const int32_t* colidx, const float* vals,
             const float* X, float* Y,
             int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy,
             int32_t W, int32_t mode, uint64_t seed, void* stream);
+
+/*
+ * es_spmm_norm -- es_spmm with the row factor `norm` (an es_norm_t) applied to
+ * every output row before it is stored.  es_spmm is es_spmm_norm with
+ * ES_NORM_NONE; every other argument and rule is the same.  The paper gives no
+ * formula for its in-kernel normalisation; the factors above are this
+ * library's definition of it.
+ */
+int es_spmm_norm(const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                 const float* X, float* Y,
+                 int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy,
+                 int32_t W, int32_t mode, uint64_t seed, int32_t norm, void* stream);
 
 /*
  * es_spmm_sample_edges -- the sampler of Section 4.2 / 4.4 on its own, for

@@ -17,6 +17,7 @@ import numpy as np
 
 FULL, BUCKET, FASTRAND = 0, 1, 2
 MODES = {"full": FULL, "bucket": BUCKET, "fastrand": FASTRAND}
+NORMS = {"none": 0, "mean": 1, "rsqrt": 2, "rescale": 3}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "es_oracle.c")
@@ -49,7 +50,9 @@ def _load():
     lib.es_oracle_spmm.restype = ctypes.c_int
     lib.es_oracle_spmm.argtypes = [i32p, i32p, f32p, f32p, ctypes.c_int64, ctypes.c_int64,
                                    ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
-                                   ctypes.c_uint64, i64p, ctypes.c_int64, f64p, f64p]
+                                   ctypes.c_uint64, ctypes.c_int32, i64p, ctypes.c_int64, f64p, f64p]
+    lib.es_oracle_row_factor.restype = ctypes.c_double
+    lib.es_oracle_row_factor.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64]
     lib.es_oracle_sample_index.restype = ctypes.c_int64
     lib.es_oracle_sample_index.argtypes = [ctypes.c_int32, ctypes.c_uint64, ctypes.c_int64,
                                            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]
@@ -133,8 +136,16 @@ def kept(rowptr, W: int, mode, seed: int = 0, rows: Optional[Sequence[int]] = No
     return pos, cnt
 
 
+def row_factor(norm, n: int, k: int) -> float:
+    return float(_load().es_oracle_row_factor(_norm(norm), n, k))
+
+
+def _norm(norm) -> int:
+    return NORMS[norm] if isinstance(norm, str) else int(norm)
+
+
 def spmm(rowptr, colidx, vals, X, F: int, W: int, mode, seed: int = 0,
-         rows: Optional[Sequence[int]] = None, want_denom: bool = True):
+         rows: Optional[Sequence[int]] = None, want_denom: bool = True, norm="none"):
     """(Yref [nrows x F] float64, denom [nrows x F] float64 or None)."""
     rowptr = _c(rowptr, np.int32)
     colidx = _c(colidx, np.int32)
@@ -148,7 +159,7 @@ def spmm(rowptr, colidx, vals, X, F: int, W: int, mode, seed: int = 0,
     D = np.empty((nrows, F), dtype=np.float64) if want_denom else None
     rc = _load().es_oracle_spmm(_ptr(rowptr, ctypes.c_int32), _ptr(colidx, ctypes.c_int32),
                                 _ptr(vals_a, ctypes.c_float), _ptr(X, ctypes.c_float),
-                                ldx, N, int(F), int(W), _mode(mode), int(seed),
+                                ldx, N, int(F), int(W), _mode(mode), int(seed), _norm(norm),
                                 _ptr(rows_a, ctypes.c_int64), nrows,
                                 _ptr(Y, ctypes.c_double), _ptr(D, ctypes.c_double))
     if rc != 0:

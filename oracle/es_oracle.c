@@ -36,6 +36,17 @@
  *     is nothing in the paper to pin it against (it is pinned only by its
  *     written definition above and the distinctness / subset invariants).
  *
+ * Row normalisation (Section 6.1: sampling changes a row's number of edges, so
+ * the degree normalisation a GNN framework applies outside the SpMM has to move
+ * into the kernel; the paper prints no formula).  Reading: the row's sum is
+ * multiplied by a factor of its stored count n and kept count k --
+ *   NONE 1;  MEAN 1/k (mean over the kept neighbours, GraphSage-mean);
+ *   RSQRT 1/sqrt(k) (destination side of the symmetric GCN normalisation);
+ *   RESCALE n/k (estimate of the full row sum);  rows with k = 0 stay 0.
+ * This part has nothing in the paper to be pinned to ("parity unpinned" against
+ * the authors' kernel); it is pinned to its written definition by dense
+ * brute force and by the closed forms it implies.
+ *
  * Sums are accumulated in double, slot by slot in slot order.  `denom` is
  * sum_i |vals[kept_i]| * |X[colidx[kept_i], c]|, the scale of the parity bound.
  *
@@ -50,6 +61,7 @@
 #endif
 
 enum { ORACLE_FULL = 0, ORACLE_BUCKET = 1, ORACLE_FASTRAND = 2 };
+enum { ORACLE_NORM_NONE = 0, ORACLE_NORM_MEAN = 1, ORACLE_NORM_RSQRT = 2, ORACLE_NORM_RESCALE = 3 };
 
 /* One output of SplitMix64: the state is advanced by the golden-ratio
  * increment, then mixed (Steele, Lea, Flood 2014; Vigna's public-domain
@@ -105,6 +117,16 @@ int64_t es_oracle_sample_index(int32_t mode, uint64_t seed, int64_t row,
     return (int64_t)((off + (uint64_t)i * P) % (uint64_t)n);
 }
 
+/* Row factor of the normalisation (see the header comment). */
+double es_oracle_row_factor(int32_t norm, int64_t n, int64_t k)
+{
+    if (norm == ORACLE_NORM_NONE) return 1.0;
+    if (k == 0) return 0.0;
+    if (norm == ORACLE_NORM_MEAN) return 1.0 / (double)k;
+    if (norm == ORACLE_NORM_RSQRT) return 1.0 / sqrt((double)k);
+    return (double)n / (double)k;
+}
+
 static int bad_mode(int32_t mode)
 {
     return mode != ORACLE_FULL && mode != ORACLE_BUCKET && mode != ORACLE_FASTRAND;
@@ -145,16 +167,18 @@ int es_oracle_kept(const int32_t *rowptr, int64_t N, int64_t W, int32_t mode,
 /*
  * Yref[j, c] and denom[j, c] (both [nrows x F], double) for the listed rows
  * (rows == NULL: rows 0 .. nrows-1).  vals == NULL means every stored entry
- * is 1 (unweighted graph, Section 2.2).  denom may be NULL.
+ * is 1 (unweighted graph, Section 2.2).  denom may be NULL.  `norm` selects
+ * the row factor applied to both the sum and its denominator.
  * Returns 0, or -1 on a bad argument.
  */
 int es_oracle_spmm(const int32_t *rowptr, const int32_t *colidx, const float *vals,
                    const float *X, int64_t ldx, int64_t N, int64_t F, int64_t W,
-                   int32_t mode, uint64_t seed, const int64_t *rows, int64_t nrows,
-                   double *Yref, double *denom)
+                   int32_t mode, uint64_t seed, int32_t norm, const int64_t *rows,
+                   int64_t nrows, double *Yref, double *denom)
 {
     if (!rowptr || !X || !Yref || N < 0 || F < 1 || ldx < F || nrows < 0 || bad_mode(mode))
         return -1;
+    if (norm < ORACLE_NORM_NONE || norm > ORACLE_NORM_RESCALE) return -1;
     if (mode != ORACLE_FULL && W < 1) return -1;
     if (!colidx && N > 0 && rowptr[N] > 0) return -1;
     if (rows)
@@ -181,6 +205,11 @@ int es_oracle_spmm(const int32_t *rowptr, const int32_t *colidx, const float *va
                 double aa = fabs(a);
                 for (int64_t c = 0; c < F; ++c) d[c] += aa * fabs((double)x[c]);
             }
+        }
+        if (norm != ORACLE_NORM_NONE) {
+            double f = es_oracle_row_factor(norm, n, k);
+            for (int64_t c = 0; c < F; ++c) y[c] *= f;
+            if (d) for (int64_t c = 0; c < F; ++c) d[c] *= f;
         }
     }
     return 0;

@@ -9,10 +9,12 @@ from .binding import (  # noqa: F401
     ES_FASTRAND,
     ES_FULL,
     MODES,
+    NORMS,
     EsSpmmError,
     es_spmm,
     es_spmm_materialize,
     es_spmm_max_W,
+    es_spmm_norm,
     es_spmm_sample_edges,
     es_spmm_set_long_row_threshold,
     es_spmm_set_rows_per_wave,

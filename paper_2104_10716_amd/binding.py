@@ -8,6 +8,8 @@ from typing import Optional
 
 ES_FULL, ES_BUCKET, ES_FASTRAND = 0, 1, 2
 MODES = {"full": ES_FULL, "bucket": ES_BUCKET, "fastrand": ES_FASTRAND}
+ES_NORM_NONE, ES_NORM_MEAN, ES_NORM_RSQRT, ES_NORM_RESCALE = 0, 1, 2, 3
+NORMS = {"none": ES_NORM_NONE, "mean": ES_NORM_MEAN, "rsqrt": ES_NORM_RSQRT, "rescale": ES_NORM_RESCALE}
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libes_spmm.so")
@@ -40,6 +42,10 @@ def load_library():
     lib.es_spmm.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
                             ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                             ctypes.c_uint64, vp]
+    lib.es_spmm_norm.restype = ctypes.c_int
+    lib.es_spmm_norm.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                 ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                 ctypes.c_uint64, ctypes.c_int32, vp]
     lib.es_spmm_sample_edges.restype = ctypes.c_int
     lib.es_spmm_sample_edges.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                          ctypes.c_uint64, ctypes.c_int32, vp, vp, vp]
@@ -107,15 +113,8 @@ def es_spmm_set_long_row_threshold(entries: int) -> None:
         raise EsSpmmError(rc, "es_spmm_set_long_row_threshold")
 
 
-def es_spmm(rowptr, colidx, vals, X, Y, W: int, mode, seed: int = 0, F: Optional[int] = None,
-            stream=None, nnz: Optional[int] = None):
-    """Y[:, :F] = sample_W(A) @ X[:, :F] on the tensors' device; returns Y.
-    rowptr/colidx int32, vals float32 or None, X/Y 2-D float32 with unit column
-    stride (row stride = leading dimension).  Enqueued on `stream` (default:
-    torch's current stream); not synchronised.  `nnz` (default: len(colidx)) is
-    only the launch-shape hint of the C ABI."""
+def _spmm_args(rowptr, colidx, vals, X, Y, F, nnz):
     import torch
-    lib = load_library()
     if X.dim() != 2 or Y.dim() != 2 or X.stride(1) != 1 or Y.stride(1) != 1:
         raise ValueError("X and Y must be 2-D with contiguous columns")
     N = rowptr.numel() - 1
@@ -131,12 +130,36 @@ def es_spmm(rowptr, colidx, vals, X, Y, W: int, mode, seed: int = 0, F: Optional
         raise ValueError("vals and colidx differ in length")
     if nnz is None:
         nnz = colidx.numel()
-    rc = lib.es_spmm(_dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(colidx, torch.int32, "colidx"),
-                     _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(X, torch.float32, "X"),
-                     _dev_ptr(Y, torch.float32, "Y"), N, nnz, int(F), int(ldx), int(ldy),
-                     int(W), _mode(mode), int(seed) & 0xFFFFFFFFFFFFFFFF, _stream_ptr(stream))
+    return (_dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(colidx, torch.int32, "colidx"),
+            _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(X, torch.float32, "X"),
+            _dev_ptr(Y, torch.float32, "Y"), N, nnz, int(F), int(ldx), int(ldy))
+
+
+def es_spmm(rowptr, colidx, vals, X, Y, W: int, mode, seed: int = 0, F: Optional[int] = None,
+            stream=None, nnz: Optional[int] = None):
+    """Y[:, :F] = sample_W(A) @ X[:, :F] on the tensors' device; returns Y.
+    rowptr/colidx int32, vals float32 or None, X/Y 2-D float32 with unit column
+    stride (row stride = leading dimension).  Enqueued on `stream` (default:
+    torch's current stream); not synchronised.  `nnz` (default: len(colidx)) is
+    only the launch-shape hint of the C ABI."""
+    lib = load_library()
+    args = _spmm_args(rowptr, colidx, vals, X, Y, F, nnz)
+    rc = lib.es_spmm(*args, int(W), _mode(mode), int(seed) & 0xFFFFFFFFFFFFFFFF, _stream_ptr(stream))
     if rc != 0:
         raise EsSpmmError(rc, "es_spmm")
+    return Y
+
+
+def es_spmm_norm(rowptr, colidx, vals, X, Y, W: int, mode, seed: int = 0, norm="none",
+                 F: Optional[int] = None, stream=None, nnz: Optional[int] = None):
+    """es_spmm with a row factor ("none", "mean", "rsqrt", "rescale") applied in the kernel."""
+    lib = load_library()
+    args = _spmm_args(rowptr, colidx, vals, X, Y, F, nnz)
+    nm = NORMS[norm] if isinstance(norm, str) else int(norm)
+    rc = lib.es_spmm_norm(*args, int(W), _mode(mode), int(seed) & 0xFFFFFFFFFFFFFFFF, nm,
+                          _stream_ptr(stream))
+    if rc != 0:
+        raise EsSpmmError(rc, "es_spmm_norm")
     return Y
 
 

@@ -52,6 +52,7 @@ struct Args {
     uint64_t seed;
     int32_t F, ldx, ldy, W, mode, logR;
     int32_t long_k;            // rows keeping more entries go to the long-row kernel
+    int32_t norm;              // es_norm_t: row factor applied before the store
     uint32_t nblocks;          // workgroups that carry rows
     uint32_t blocks_per_xcd;   // ceil(nblocks / 8)
 };
@@ -172,6 +173,7 @@ template <bool ALIGNED> struct Pack<4, ALIGNED> {
         v.x = fmaf(a, x.v.x, v.x); v.y = fmaf(a, x.v.y, v.y);
         v.z = fmaf(a, x.v.z, v.z); v.w = fmaf(a, x.v.w, v.w);
     }
+    __device__ __forceinline__ void scale(float f) { v.x *= f; v.y *= f; v.z *= f; v.w *= f; }
     __device__ __forceinline__ void add_xor(int mask)
     {
         v.x += __shfl_xor(v.x, mask, kWaveSize); v.y += __shfl_xor(v.y, mask, kWaveSize);
@@ -185,6 +187,7 @@ template <bool ALIGNED> struct Pack<1, ALIGNED> {
     __device__ __forceinline__ void store(float* p, int) const { *p = v; }
     __device__ __forceinline__ void atomic_add(float* p, int) const { unsafeAtomicAdd(p, v); }
     __device__ __forceinline__ void fma(float a, const Pack& x) { v = fmaf(a, x.v, v); }
+    __device__ __forceinline__ void scale(float f) { v *= f; }
     __device__ __forceinline__ void add_xor(int mask) { v += __shfl_xor(v, mask, kWaveSize); }
 };
 
@@ -291,6 +294,17 @@ __device__ __forceinline__ int kept_count(int mode, int n, int W)
     return (mode == ES_FULL) ? n : min(n, W);
 }
 
+// Row factor of the in-kernel normalisation (Section 6.1): a function of the
+// row's stored count n and kept count k; rows that keep nothing stay zero.
+__device__ __forceinline__ float row_factor(int norm, int n, int k)
+{
+    if (norm == ES_NORM_NONE) return 1.0f;
+    if (k == 0) return 0.0f;
+    if (norm == ES_NORM_MEAN) return 1.0f / (float)k;
+    if (norm == ES_NORM_RSQRT) return 1.0f / sqrtf((float)k);
+    return (float)n / (float)k;
+}
+
 // ---------------------------------------------------------------------------
 // Fused kernel (Algorithm 1).  G lanes x CH chunks x VEC floats cover one block
 // of G*CH*VEC feature columns (blockIdx.y selects the block).
@@ -328,8 +342,8 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
         base = a.rowptr[r];
         n = a.rowptr[r + 1] - base;
     }
-    int k = kept_count(a.mode, n, a.W);
-    if (k > a.long_k) k = 0;                     // long-row kernel adds this row; store zeros here
+    const int k_row = kept_count(a.mode, n, a.W);
+    const int k = (k_row > a.long_k) ? 0 : k_row;  // long-row kernel adds such a row; store zeros here
 
     LaneCols<G, CH, VEC, ALIGNED> cols;
     cols.init(blockIdx.y * (G * CH * VEC), l, a.F);
@@ -356,6 +370,11 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
     }
     if (rvalid && e == 0) {
         float* y = a.Y + r * (int64_t)a.ldy;
+        if (a.norm != ES_NORM_NONE) {
+            const float f = row_factor(a.norm, n, k_row);
+#pragma unroll
+            for (int ch = 0; ch < CH; ++ch) acc[ch].scale(f);
+        }
 #pragma unroll
         for (int ch = 0; ch < CH; ++ch)
             if (cols.ok[ch]) acc[ch].store(y + cols.off[ch], cols.first[ch]);
@@ -458,6 +477,11 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_long_rows_kernel(const 
         }
         if (e == 0) {
             float* y = a.Y + r * (int64_t)a.ldy;
+            if (a.norm != ES_NORM_NONE) {
+                const float f = row_factor(a.norm, n, k);
+#pragma unroll
+                for (int ch = 0; ch < CH; ++ch) acc[ch].scale(f);
+            }
 #pragma unroll
             for (int ch = 0; ch < CH; ++ch)
                 if (cols.ok[ch]) acc[ch].atomic_add(y + cols.off[ch], cols.first[ch]);
@@ -747,6 +771,15 @@ int es_spmm(const int32_t* rowptr, const int32_t* colidx, const float* vals, con
             float* Y, int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W,
             int32_t mode, uint64_t seed, void* stream)
 {
+    return es_spmm_norm(rowptr, colidx, vals, X, Y, N, nnz, F, ldx, ldy, W, mode, seed, ES_NORM_NONE,
+                        stream);
+}
+
+int es_spmm_norm(const int32_t* rowptr, const int32_t* colidx, const float* vals, const float* X,
+                 float* Y, int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W,
+                 int32_t mode, uint64_t seed, int32_t norm, void* stream)
+{
+    if (norm < ES_NORM_NONE || norm > ES_NORM_RESCALE) return ES_ERR_INVALID_ARG;
     if (N < 0 || nnz < 0 || nnz > INT32_MAX || F < 1 || ldx < F || ldy < F) return ES_ERR_INVALID_ARG;
     if (mode != ES_FULL && mode != ES_BUCKET && mode != ES_FASTRAND) return ES_ERR_INVALID_ARG;
     if (mode != ES_FULL && W < 1) return ES_ERR_INVALID_ARG;
@@ -781,7 +814,7 @@ int es_spmm(const int32_t* rowptr, const int32_t* colidx, const float* vals, con
     a.rowptr = rowptr; a.colidx = colidx; a.vals = vals; a.X = X; a.Y = Y;
     a.N = N; a.seed = seed; a.F = F; a.ldx = ldx; a.ldy = ldy;
     a.W = (mode == ES_FULL) ? INT32_MAX : W;
-    a.mode = mode; a.logR = logR;
+    a.mode = mode; a.logR = logR; a.norm = norm;
     a.nblocks = (uint32_t)nblocks; a.blocks_per_xcd = (uint32_t)per_xcd;
 
     // rows that may keep more than long_k entries exist only in full mode or

@@ -16,12 +16,15 @@ class DeviceCSR:
         self.N = rowptr.shape[0] - 1
         self.F = X.shape[1] if F is None else F
 
-    def run(self, W, mode, seed=0, ldy=None):
+    def run(self, W, mode, seed=0, ldy=None, norm=None):
         import torch
         import paper_2104_10716_amd as es
         ldy = self.F if ldy is None else ldy
         Y = torch.full((self.N, ldy), float("nan"), dtype=torch.float32, device=self.X.device)
-        es.es_spmm(self.rowptr, self.colidx, self.vals, self.X, Y, W, mode, seed, F=self.F)
+        if norm is None:
+            es.es_spmm(self.rowptr, self.colidx, self.vals, self.X, Y, W, mode, seed, F=self.F)
+        else:
+            es.es_spmm_norm(self.rowptr, self.colidx, self.vals, self.X, Y, W, mode, seed, norm, F=self.F)
         torch.cuda.synchronize()
         return Y
 
@@ -49,15 +52,16 @@ def check_Y(Y_gpu, Yref, denom, what, tol=TOL):
     return float(rel.max()) if rel.size else 0.0
 
 
-def check_against_oracle(d, W, mode, seed=0, rows=None, ldy=None, what=""):
+def check_against_oracle(d, W, mode, seed=0, rows=None, ldy=None, what="", norm=None):
     """Run es_spmm on DeviceCSR `d` and compare (all rows, or the listed rows)."""
     import oracle
-    Y = d.run(W, mode, seed, ldy=ldy)
+    Y = d.run(W, mode, seed, ldy=ldy, norm=norm)
     Yh = Y.cpu().numpy()
     if ldy is not None and ldy > d.F:
         assert np.isnan(Yh[:, d.F:]).all(), f"{what}: columns beyond F were written"
     Yh = Yh[:, :d.F]
-    Yref, den = oracle.spmm(d.h_rowptr, d.h_colidx, d.h_vals, d.h_X, d.F, W, mode, seed, rows=rows)
+    Yref, den = oracle.spmm(d.h_rowptr, d.h_colidx, d.h_vals, d.h_X, d.F, W, mode, seed, rows=rows,
+                            norm="none" if norm is None else norm)
     if rows is not None:
         Yh = Yh[np.asarray(rows)]
     return check_Y(Yh, Yref, den, what or f"{mode} W={W} seed={seed}")

@@ -168,6 +168,28 @@ def test_degenerate_inputs(es):
     assert torch.equal(Y, du.run(2, "fastrand", 5))
 
 
+@pytest.mark.parametrize("norm", ["none", "mean", "rsqrt", "rescale"])
+def test_in_kernel_normalisation(es, norm):
+    """es_spmm_norm (Section 6.1): row factor of (n, k) applied in the kernel,
+    on ordinary rows, on rows sent through the long-row path, and at full size."""
+    from gpu_util import DeviceCSR, check_against_oracle
+    for F in (16, 41):
+        rowptr, colidx, vals, X = _random_graph(900, 25.0, seed=F, F=F, empty_frac=0.1)
+        d = DeviceCSR(rowptr, colidx, vals, X)
+        for thr in (0, 9):
+            es.es_spmm_set_long_row_threshold(thr)
+            for mode, W in (("full", 0), ("bucket", 6), ("fastrand", 6), ("fastrand", 20), ("fastrand", 1000)):
+                check_against_oracle(d, W, mode, 11, norm=norm, what=f"norm={norm} {mode} W={W} F={F} thr={thr}")
+        es.es_spmm_set_long_row_threshold(0)
+    w = _workload(2)
+    d = DeviceCSR(w.rowptr, w.colidx, w.vals, w.X)
+    for mode, W in (("full", 0), ("fastrand", 16), ("bucket", 64)):
+        worst = check_against_oracle(d, W, mode, 0, norm=norm, what=f"cfg2 norm={norm} {mode} W={W}")
+        _say(f"cfg2 norm={norm} {mode} W={W}: max normalised error {worst:.2e}")
+    with pytest.raises(es.EsSpmmError):
+        d.run(4, "bucket", norm=7)
+
+
 def test_hip_graph_capture_and_replay(es):
     """es_spmm only enqueues kernels, so a caller can capture it in a HIP graph.
     Replays (with eager work and synchronisations in between) must reproduce the

@@ -265,3 +265,54 @@ def test_bad_arguments_are_rejected():
         oracle.spmm(rowptr, colidx, None, X, 4, 4, "bucket", rows=[16])
     with pytest.raises(ValueError):
         oracle.kept(rowptr, 0, "fastrand")
+
+
+# --------------------------------------------------------------------------
+# row normalisation (Section 6.1; this build's reading, see the oracle header)
+# --------------------------------------------------------------------------
+def test_row_factor_closed_forms():
+    assert oracle.row_factor("none", 10, 4) == 1.0
+    assert oracle.row_factor("mean", 10, 4) == 0.25
+    assert oracle.row_factor("rsqrt", 10, 4) == 0.5
+    assert oracle.row_factor("rescale", 10, 4) == 2.5
+    for norm in ("mean", "rsqrt", "rescale"):
+        assert oracle.row_factor(norm, 0, 0) == 0.0
+    assert oracle.row_factor("none", 0, 0) == 1.0
+
+
+@pytest.mark.parametrize("norm", ["mean", "rsqrt", "rescale"])
+@pytest.mark.parametrize("mode,W", [("bucket", 3), ("fastrand", 3), ("full", 0), ("fastrand", 50)])
+def test_normalised_product_vs_dense_bruteforce(norm, mode, W):
+    n, F = 44, 6
+    rowptr, colidx = random_csr(n, 7.0, seed=17, empty_frac=0.15)
+    rng = np.random.default_rng(3)
+    vals = rng.standard_normal(colidx.size).astype(np.float32)
+    X = rng.standard_normal((n, F)).astype(np.float32)
+    pos, cnt = oracle.kept(rowptr, W, mode, 4)
+    A = _dense_from_kept(rowptr, colidx, vals, pos, cnt, n)
+    deg = np.diff(rowptr).astype(np.float64)
+    k = cnt.astype(np.float64)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        f = {"mean": 1.0 / k, "rsqrt": 1.0 / np.sqrt(k), "rescale": deg / k}[norm]
+    f = np.where(k > 0, f, 0.0)
+    Y, D = oracle.spmm(rowptr, colidx, vals, X, F, W, mode, 4, norm=norm)
+    Xd = X.astype(np.float64)
+    np.testing.assert_allclose(Y, f[:, None] * (A @ Xd), rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(D, f[:, None] * (np.abs(A) @ np.abs(Xd)), rtol=1e-13, atol=1e-13)
+
+
+def test_normalisation_special_cases():
+    w = make_workload(1)
+    ones = np.ones((w.N, 3), dtype=np.float32)
+    # mean of ones over any kept set is 1; rescale of unit values recovers the degree
+    for mode, W in (("bucket", 4), ("fastrand", 4), ("full", 0)):
+        Y, _ = oracle.spmm(w.rowptr, w.colidx, None, ones, 3, W, mode, 0, norm="mean")
+        assert np.allclose(Y, 1.0, rtol=1e-15)
+        Y, _ = oracle.spmm(w.rowptr, w.colidx, None, ones, 3, W, mode, 0, norm="rescale")
+        assert np.allclose(Y, np.diff(w.rowptr)[:, None], rtol=1e-15)
+    # nothing is dropped when W covers every row: rescale is the identity
+    Yn, Dn = oracle.spmm(w.rowptr, w.colidx, w.vals, w.X, w.F, w.max_degree, "fastrand", 0)
+    Yr, Dr = oracle.spmm(w.rowptr, w.colidx, w.vals, w.X, w.F, w.max_degree, "fastrand", 0, norm="rescale")
+    assert (Yn == Yr).all() and (Dn == Dr).all()
+    with pytest.raises(ValueError):
+        oracle.spmm(w.rowptr, w.colidx, w.vals, w.X, w.F, 4, "bucket", 0, norm=9)
