@@ -110,7 +110,7 @@ int es_spmm_norm(const int32_t* rowptr, const int32_t* colidx, const float* vals
  *   pos [N * W] int32 (device), cnt [N] int32 (device); N * W must be < 2^31.
  *   rows_per_wave: 0 = the library's default schedule, a power of two in
  *   [1, 64] = that many rows share a wavefront, -1 = the long-row schedule (a
- *   whole wavefront per row, the sampler restarted at every 512-slot segment).
+ *   whole wavefront per row, the sampler restarted at every 256-slot segment).
  *   Every value must produce the same output; tests sweep it.
  */
 int es_spmm_sample_edges(const int32_t* rowptr, int64_t N, int32_t W, int32_t mode,
@@ -158,7 +158,7 @@ int es_spmm_set_rows_per_wave(int32_t rows_per_wave);
 
 /*
  * Long-row threshold override.  A row keeping more than `entries` sampled
- * entries is not summed by one wavefront but cut into 512-entry segments that
+ * entries is not summed by one wavefront but cut into 256-entry segments that
  * several workgroups process in parallel (load balance for the skewed degree
  * distributions Section 4.5 "load balancing" describes; sampled rows never
  * exceed W, so this matters for ES_FULL and for very large W).  0 restores the

@@ -21,11 +21,12 @@
 //     contiguous range of rows.
 //   * Rows that keep more than `long_k` entries (full mode on skewed graphs, or a
 //     very large W) would leave one wave running long after the rest of the grid
-//     has drained.  The row kernel stores zeros for them and a second kernel
-//     splits each such row into 512-slot segments, deals the segments to the
-//     waves of kLongSplit workgroups and adds the partial sums to Y with fp32
-//     atomics.  long_k is chosen on the host so that a single wave's longest row
-//     stays a few percent of the whole launch.
+//     has drained.  The leading workgroups of the launch split each such row
+//     into 256-slot segments, deal the segments to the waves of kLongSplit
+//     workgroups and add the partial sums to Y with fp32 atomics (a small
+//     kernel zeroes those rows of Y first); the row workgroups skip them.
+//     long_k is chosen on the host so that a single wave's longest row stays a
+//     few percent of the whole launch.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -41,6 +42,9 @@ constexpr int kWaveTileStride = kTileSlots + 64;      // + one pad slot per row 
 constexpr int kNumXcd = 8;
 constexpr int kLongScanRows = 1024;                   // rows one long-row workgroup scans
 constexpr int kLongSplit = 16;                        // workgroups sharing those rows
+constexpr int kLongSeg = 256;                         // slots per long-row segment (<= kTileSlots)
+constexpr int kLongMin = 64;                          // smallest long-row threshold the host picks
+static_assert(kLongSplit % kNumXcd == 0, "long-row workgroups must not shift the XCD phase");
 
 struct Args {
     const int32_t* rowptr;
@@ -55,6 +59,7 @@ struct Args {
     int32_t norm;              // es_norm_t: row factor applied before the store
     uint32_t nblocks;          // workgroups that carry rows
     uint32_t blocks_per_xcd;   // ceil(nblocks / 8)
+    uint32_t long_blocks;      // leading workgroups that run the long-row part
 };
 
 // ---------------------------------------------------------------------------
@@ -306,22 +311,16 @@ __device__ __forceinline__ float row_factor(int norm, int n, int k)
 }
 
 // ---------------------------------------------------------------------------
-// Fused kernel (Algorithm 1).  G lanes x CH chunks x VEC floats cover one block
-// of G*CH*VEC feature columns (blockIdx.y selects the block).
+// Row part of the fused kernel (Algorithm 1) for workgroup `vb` of the row
+// grid.  G lanes x CH chunks x VEC floats cover one block of G*CH*VEC feature
+// columns (blockIdx.y selects the block).  Rows that keep more than long_k
+// entries are left to the long-row part and not stored here.
 // ---------------------------------------------------------------------------
 template <int G, int CH, int VEC, bool ALIGNED>
-__global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
+__device__ __forceinline__ void row_block(const Args& a, uint32_t vb, uint2* lds)
 {
     constexpr int LOG_G = ilog2(G);
     using P = Pack<VEC, ALIGNED>;
-
-    __shared__ uint2 lds[kWavesPerBlock * kWaveTileStride];
-
-    // XCD-aware remap: hardware deals workgroup b to XCD b % 8; give each XCD a
-    // contiguous run of row blocks.
-    const uint32_t b = blockIdx.x;
-    const uint32_t vb = (b % kNumXcd) * a.blocks_per_xcd + b / kNumXcd;
-    if (vb >= a.nblocks) return;
 
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
@@ -343,7 +342,8 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
         n = a.rowptr[r + 1] - base;
     }
     const int k_row = kept_count(a.mode, n, a.W);
-    const int k = (k_row > a.long_k) ? 0 : k_row;  // long-row kernel adds such a row; store zeros here
+    const bool is_long = k_row > a.long_k;       // summed by the long-row part
+    const int k = is_long ? 0 : k_row;
 
     LaneCols<G, CH, VEC, ALIGNED> cols;
     cols.init(blockIdx.y * (G * CH * VEC), l, a.F);
@@ -368,7 +368,7 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
 #pragma unroll
         for (int ch = 0; ch < CH; ++ch) acc[ch].add_xor(m);
     }
-    if (rvalid && e == 0) {
+    if (rvalid && !is_long && e == 0) {
         float* y = a.Y + r * (int64_t)a.ldy;
         if (a.norm != ES_NORM_NONE) {
             const float f = row_factor(a.norm, n, k_row);
@@ -382,28 +382,31 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
 }
 
 // ---------------------------------------------------------------------------
-// Long rows.  Workgroup (bx, by) scans rows [bx*1024, bx*1024+1024) for rows
-// that keep more than long_k entries, numbers their 512-slot segments with a
+// Long-row part.  Workgroup (bx, by) scans rows [bx*1024, bx*1024+1024) for rows
+// that keep more than long_k entries, numbers their 256-slot segments with a
 // prefix sum in LDS, and its 4 waves take segments gw, gw + 4*kLongSplit, ...
 // (gw = by*4 + wave).  A segment is one pass of Algorithm 1 with a whole wave on
-// the row; its partial sums are added to Y (zeroed by the row kernel) with
-// fp32 atomics, so the summation order across segments is not fixed.
+// the row; its partial sums are added to Y (zeroed beforehand by
+// es_zero_long_rows_kernel) with fp32 atomics, so the summation order across
+// segments is not fixed.
 // ---------------------------------------------------------------------------
+struct LongScratch {
+    int seg_end[kLongScanRows];                  // inclusive prefix sum of segment counts
+    int wave_total[kWavesPerBlock];
+};
+
 template <int G, int CH, int VEC, bool ALIGNED>
-__global__ void __launch_bounds__(kBlockThreads) es_spmm_long_rows_kernel(const Args a)
+__device__ __forceinline__ void long_block(const Args& a, uint32_t bx, uint32_t by, uint2* lds,
+                                           LongScratch& sc)
 {
     constexpr int LOG_G = ilog2(G);
     constexpr int kRowsPerThread = kLongScanRows / kBlockThreads;
     using P = Pack<VEC, ALIGNED>;
 
-    __shared__ uint2 lds[kWavesPerBlock * kWaveTileStride];
-    __shared__ int seg_end[kLongScanRows];       // inclusive prefix sum of segment counts
-    __shared__ int wave_total[kWavesPerBlock];
-
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = tid >> 6;
-    const int64_t row0 = (int64_t)blockIdx.x * kLongScanRows;
+    const int64_t row0 = (int64_t)bx * kLongScanRows;
 
     // thread tid owns rows row0 + tid*kRowsPerThread + i (consecutive, so the
     // prefix order is the row order)
@@ -416,7 +419,7 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_long_rows_kernel(const 
         if (r < a.N) {
             const int n = a.rowptr[r + 1] - a.rowptr[r];
             const int k = kept_count(a.mode, n, a.W);
-            if (k > a.long_k) nseg[i] = (k + kTileSlots - 1) / kTileSlots;
+            if (k > a.long_k) nseg[i] = (k + kLongSeg - 1) / kLongSeg;
         }
         mine += nseg[i];
     }
@@ -426,17 +429,17 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_long_rows_kernel(const 
         const int up = __shfl_up(incl, d, kWaveSize);
         if (lane >= d) incl += up;
     }
-    if (lane == kWaveSize - 1) wave_total[wave] = incl;
+    if (lane == kWaveSize - 1) sc.wave_total[wave] = incl;
     __syncthreads();
     int before = incl - mine;
-    for (int w = 0; w < wave; ++w) before += wave_total[w];
+    for (int w = 0; w < wave; ++w) before += sc.wave_total[w];
 #pragma unroll
     for (int i = 0; i < kRowsPerThread; ++i) {
         before += nseg[i];
-        seg_end[tid * kRowsPerThread + i] = before;
+        sc.seg_end[tid * kRowsPerThread + i] = before;
     }
     __syncthreads();
-    const int total = seg_end[kLongScanRows - 1];
+    const int total = sc.seg_end[kLongScanRows - 1];
     if (total == 0) return;
 
     const int e = lane >> LOG_G;
@@ -444,22 +447,22 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_long_rows_kernel(const 
     constexpr int E = kWaveSize / G;
     uint2* tile = lds + wave * kWaveTileStride;
     LaneCols<G, CH, VEC, ALIGNED> cols;
-    cols.init(blockIdx.z * (G * CH * VEC), l, a.F);
+    cols.init(blockIdx.y * (G * CH * VEC), l, a.F);
 
-    const int gw = blockIdx.y * kWavesPerBlock + wave;
+    const int gw = by * kWavesPerBlock + wave;
     for (int task = gw; task < total; task += kLongSplit * kWavesPerBlock) {
         int lo = 0, hi = kLongScanRows - 1;      // first row whose prefix exceeds task
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
-            if (seg_end[mid] > task) hi = mid; else lo = mid + 1;
+            if (sc.seg_end[mid] > task) hi = mid; else lo = mid + 1;
         }
-        const int seg = task - (lo ? seg_end[lo - 1] : 0);
+        const int seg = task - (lo ? sc.seg_end[lo - 1] : 0);
         const int64_t r = row0 + lo;
         const int32_t base = a.rowptr[r];
         const int n = a.rowptr[r + 1] - base;
         const int k = kept_count(a.mode, n, a.W);
-        const int t0 = seg * kTileSlots;
-        const int count = min(k - t0, kTileSlots);
+        const int t0 = seg * kLongSeg;
+        const int count = min(k - t0, kLongSeg);
 
         RowSampler sampler;
         sampler.init(a.mode, a.seed, r, (uint32_t)n, (uint32_t)a.W, (uint32_t)(t0 + lane), kWaveSize);
@@ -490,9 +493,45 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_long_rows_kernel(const 
 }
 
 // ---------------------------------------------------------------------------
+// The fused kernel.  The first a.long_blocks workgroups (dispatched first, so
+// the splitting of long rows overlaps the bulk of the rows) run the long-row
+// part; the rest run the row part, remapped so that each XCD (hardware deals
+// workgroup b to XCD b % 8; long_blocks is a multiple of 8) walks one
+// contiguous range of rows.
+// ---------------------------------------------------------------------------
+template <int G, int CH, int VEC, bool ALIGNED>
+__global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
+{
+    __shared__ uint2 lds[kWavesPerBlock * kWaveTileStride];
+    __shared__ LongScratch long_scratch;
+
+    if (blockIdx.x < a.long_blocks) {
+        long_block<G, CH, VEC, ALIGNED>(a, blockIdx.x / kLongSplit, blockIdx.x % kLongSplit, lds,
+                                        long_scratch);
+        return;
+    }
+    const uint32_t b = blockIdx.x - a.long_blocks;
+    const uint32_t vb = (b % kNumXcd) * a.blocks_per_xcd + b / kNumXcd;
+    if (vb >= a.nblocks) return;
+    row_block<G, CH, VEC, ALIGNED>(a, vb, lds);
+}
+
+// Zeroes Y for the rows the long-row part will accumulate into with atomics.
+// One thread per row; such rows are rare by construction of long_k.
+__global__ void __launch_bounds__(kBlockThreads) es_zero_long_rows_kernel(const Args a)
+{
+    const int64_t r = (int64_t)blockIdx.x * kBlockThreads + threadIdx.x;
+    if (r >= a.N) return;
+    const int n = a.rowptr[r + 1] - a.rowptr[r];
+    if (kept_count(a.mode, n, a.W) <= a.long_k) return;
+    float* y = a.Y + r * (int64_t)a.ldy;
+    for (int c = 0; c < a.F; ++c) y[c] = 0.0f;
+}
+
+// ---------------------------------------------------------------------------
 // Sampler export: identical team / tile schedule, sink writes CSR positions.
 // logR < 0 selects the long-row schedule instead: a whole wave per row, one
-// freshly initialised sampler per 512-slot segment.
+// freshly initialised sampler per kLongSeg-slot segment.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kBlockThreads)
 es_sample_edges_kernel(const int32_t* __restrict__ rowptr, int64_t N, int32_t W, int32_t mode,
@@ -506,7 +545,7 @@ es_sample_edges_kernel(const int32_t* __restrict__ rowptr, int64_t N, int32_t W,
     const int team = kWaveSize >> logR;
     const int rs = lane >> (6 - logR);
     const int t = lane & (team - 1);
-    const int T = kTileSlots >> logR;
+    const int T = segmented ? kLongSeg : (kTileSlots >> logR);
     const int64_t r = ((((int64_t)blockIdx.x * kWavesPerBlock) + wave) << logR) + rs;
     if (r >= N) return;
     const int32_t base = rowptr[r];
@@ -697,16 +736,16 @@ int pick_logR(const Shape& s, double mean_kept)
 }
 
 template <int G, int CH, int VEC, bool ALIGNED>
-hipError_t launch(const Args& a, dim3 grid, dim3 long_grid, hipStream_t st)
+hipError_t launch(const Args& a, dim3 grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((es_spmm_kernel<G, CH, VEC, ALIGNED>), grid, dim3(kBlockThreads), 0, st, a);
-    hipError_t err = hipGetLastError();
-    if (err == hipSuccess && long_grid.x > 0) {
-        hipLaunchKernelGGL((es_spmm_long_rows_kernel<G, CH, VEC, ALIGNED>), long_grid,
-                           dim3(kBlockThreads), 0, st, a);
-        err = hipGetLastError();
+    if (a.long_blocks > 0) {
+        const uint32_t zb = (uint32_t)((a.N + kBlockThreads - 1) / kBlockThreads);
+        hipLaunchKernelGGL(es_zero_long_rows_kernel, dim3(zb), dim3(kBlockThreads), 0, st, a);
+        const hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return err;
     }
-    return err;
+    hipLaunchKernelGGL((es_spmm_kernel<G, CH, VEC, ALIGNED>), grid, dim3(kBlockThreads), 0, st, a);
+    return hipGetLastError();
 }
 
 // Longest row one wave may own.  A wave retires about E*U entries per memory
@@ -717,9 +756,9 @@ int32_t pick_long_k(const Shape& s, int logR, double entries, int F)
     const int U = 8 / s.CH;
     const int E = (64 >> logR) / s.G;
     const double k = (double)E * U * entries * (4.0 * F + 8.0) / 2.4e8;
-    if (k >= (double)(INT32_MAX - kTileSlots)) return INT32_MAX;
-    int32_t v = ((int32_t)k / kTileSlots) * kTileSlots;
-    return v < kTileSlots ? kTileSlots : v;
+    if (k >= (double)(INT32_MAX - kLongMin)) return INT32_MAX;
+    const int32_t v = ((int32_t)k / kLongMin) * kLongMin;
+    return v < kLongMin ? kLongMin : v;
 }
 
 int32_t g_force_logR = -1;   // es_spmm_set_rows_per_wave override; -1 = heuristic
@@ -821,17 +860,23 @@ int es_spmm_norm(const int32_t* rowptr, const int32_t* colidx, const float* vals
     // for W above the bound (nnz is a hint, so it does not gate the launch)
     double entries = (double)nnz;
     if (mode != ES_FULL && entries > (double)N * W) entries = (double)N * W;
-    a.long_k = g_force_long_k > 0 ? g_force_long_k : pick_long_k(s, logR, entries, F);
+    a.long_k = pick_long_k(s, logR, entries, F);
+    // the long-row part costs a second small launch and a scan of the row
+    // pointers; below one tile per row that is more than the tail it removes
+    if (mode != ES_FULL && a.long_k < kTileSlots) a.long_k = kTileSlots;
+    if (g_force_long_k > 0) a.long_k = g_force_long_k;
     const bool may_be_long = mode == ES_FULL || W > a.long_k;
-    const int64_t long_x = (N + kLongScanRows - 1) / kLongScanRows;
+    const int64_t long_blocks =
+        may_be_long ? ((N + kLongScanRows - 1) / kLongScanRows) * kLongSplit : 0;
+    if (grid_x + long_blocks > INT32_MAX) return ES_ERR_UNSUPPORTED;
+    a.long_blocks = (uint32_t)long_blocks;
 
-    const dim3 grid((uint32_t)grid_x, (uint32_t)grid_y);
-    const dim3 long_grid(may_be_long ? (uint32_t)long_x : 0u, kLongSplit, (uint32_t)grid_y);
+    const dim3 grid((uint32_t)(grid_x + long_blocks), (uint32_t)grid_y);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t err = hipErrorInvalidValue;
 #define ES_CASE(G_, CH_, V_, A_)                                                   \
     if (s.G == G_ && s.CH == CH_ && s.vec == V_ && s.aligned == A_)                \
-        err = launch<G_, CH_, V_, A_>(a, grid, long_grid, st);
+        err = launch<G_, CH_, V_, A_>(a, grid, st);
     ES_CASE(4, 1, 4, true) ES_CASE(8, 1, 4, true) ES_CASE(16, 1, 4, true) ES_CASE(32, 1, 4, true)
     ES_CASE(64, 1, 4, true) ES_CASE(64, 2, 4, true) ES_CASE(64, 4, 4, true)
     ES_CASE(4, 1, 4, false) ES_CASE(8, 1, 4, false) ES_CASE(16, 1, 4, false) ES_CASE(32, 1, 4, false)
