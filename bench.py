@@ -256,7 +256,7 @@ def main() -> int:
             result["cpu_baseline"] = (cpu_baseline(dw, calls) if args.config == 2
                                       else cpu_baseline_rows(dw, calls))
             log(f"cpu baseline: {result['cpu_baseline']}")
-        extra = []
+        extra = [tiny_config1(dev)]
         for cfg in (3, 4):
             if cfg == args.config:
                 continue
@@ -272,6 +272,13 @@ def main() -> int:
                 log(f"  cfg{cfg} {r['mode']:8s} W={r['W']:4d}: {r['ms']:.3f} ms  {r['eff_GBps']:.0f} GB/s "
                     f"({100 * r['frac_hbm_peak']:.1f}% of peak)  cold {r['ms_cold']} ms  x{r['speedup_vs_full']} vs full")
             if cfg == 3:
+                big = per_call_table(dw, [("bucket", 1792), ("bucket", 2304), ("fastrand", 1792),
+                                          ("full", 0)], 5, None, 0)
+                extra.append({"workload": "config-3 graph at the widths the paper needs for Bucket on its "
+                                          "densest graph (S = 1792, 2304)", "calls": big[:-1]})
+                for r in big[:-1]:
+                    log(f"  cfg3 {r['mode']:8s} W={r['W']:4d}: {r['ms']:.3f} ms  {r['eff_GBps']:.0f} GB/s  "
+                        f"x{r['speedup_vs_full']} vs full")
                 extra.append(presampled_ablation(dw, dev))
                 extra.append(gcn_feature_sweep(dw, dev, flush))
         result["extra"] = extra
@@ -281,6 +288,35 @@ def main() -> int:
 
     print(json.dumps(result), flush=True)
     return 0
+
+
+def tiny_config1(dev):
+    """configs[0]: ~1 MB moved per call, so a call is launch-bound; report the
+    per-call time and the time of the whole sweep replayed as one HIP graph."""
+    import torch
+    from workloads import make_workload
+    w = make_workload(1)
+    dw = DeviceWorkload(w, dev)
+    calls = dw.calls(w.Ws)
+    rows = per_call_table(dw, calls, 50, None, 0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for mode, W in calls:
+            dw.launch(mode, W)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for mode, W in calls:
+            dw.launch(mode, W)
+    t_graph = _time_fn(g.replay, reps=50)
+    out = {"workload": "configs[0] tiny GCN aggregation: N=2708, F=16 (launch-bound)", "N": dw.N,
+           "nnz": dw.nnz, "F": dw.F, "calls": rows,
+           "sweep_as_hip_graph_ms": round(t_graph, 4), "calls_in_graph": len(calls)}
+    log(f"  cfg1: per-call {min(r['ms'] for r in rows):.4f}-{max(r['ms'] for r in rows):.4f} ms; "
+        f"{len(calls)}-call sweep as one HIP graph {t_graph:.4f} ms")
+    return out
 
 
 def _time_fn(fn, reps=10, warm=2):
