@@ -125,20 +125,24 @@ def per_call_table(dw, calls, reps, flush, cold_reps):
     return rows
 
 
-def cpu_baseline(dw, calls):
-    """The CPU oracle, as it stands, on one whole step of the same workload."""
+def cpu_baseline(dw, calls, min_seconds=10.0, max_steps=200):
+    """The CPU oracle, as it stands, on whole steps of the same workload,
+    repeated until about `min_seconds` of CPU work have been timed."""
     import oracle
     w = dw.w
-    X = w.X
+    step_bytes = sum(algorithmic_bytes(dw.N, dw.nnz_kept(mode, W), dw.F) for mode, W in calls)
+    steps = 0
     t0 = time.perf_counter()
-    total_bytes = 0
-    for mode, W in calls:
-        oracle.spmm(w.rowptr, w.colidx, w.vals, X, dw.F, W, mode, 0, want_denom=False)
-        total_bytes += algorithmic_bytes(dw.N, dw.nnz_kept(mode, W), dw.F)
-    dt = time.perf_counter() - t0
-    return {"value": round(total_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.threads(),
+    while True:
+        for mode, W in calls:
+            oracle.spmm(w.rowptr, w.colidx, w.vals, w.X, dw.F, W, mode, 0, want_denom=False)
+        steps += 1
+        dt = time.perf_counter() - t0
+        if dt >= min_seconds or steps >= max_steps:
+            break
+    return {"value": round(steps * step_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.threads(),
             "kind": "oracle", "seconds": round(dt, 2),
-            "sample": "one whole step (every call of the sweep, all rows), fp64 accumulation"}
+            "sample": f"{steps} whole steps (every call of the sweep, all rows), fp64 accumulation"}
 
 
 def cpu_baseline_rows(dw, calls, target_seconds=20.0):

@@ -51,6 +51,10 @@ def _load():
     lib.es_oracle_spmm.argtypes = [i32p, i32p, f32p, f32p, ctypes.c_int64, ctypes.c_int64,
                                    ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
                                    ctypes.c_uint64, ctypes.c_int32, i64p, ctypes.c_int64, f64p, f64p]
+    lib.es_oracle_spmm_backward.restype = ctypes.c_int
+    lib.es_oracle_spmm_backward.argtypes = [i32p, i32p, f32p, f32p, ctypes.c_int64, ctypes.c_int64,
+                                            ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                            ctypes.c_uint64, ctypes.c_int32, f64p, f64p]
     lib.es_oracle_row_factor.restype = ctypes.c_double
     lib.es_oracle_row_factor.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64]
     lib.es_oracle_sample_index.restype = ctypes.c_int64
@@ -165,3 +169,23 @@ def spmm(rowptr, colidx, vals, X, F: int, W: int, mode, seed: int = 0,
     if rc != 0:
         raise ValueError("es_oracle_spmm: bad argument")
     return Y, D
+
+
+def spmm_backward(rowptr, colidx, vals, dY, F: int, W: int, mode, seed: int = 0, norm="none",
+                  want_denom: bool = True):
+    """(dX [N x F] float64, denom [N x F] float64 or None): transposed sampled product."""
+    rowptr = _c(rowptr, np.int32)
+    colidx = _c(colidx, np.int32)
+    vals_a = None if vals is None else _c(vals, np.float32)
+    dY = _c(dY, np.float32)
+    N = rowptr.shape[0] - 1
+    ldy = dY.shape[1] if dY.ndim == 2 else F
+    dX = np.empty((N, F), dtype=np.float64)
+    D = np.empty((N, F), dtype=np.float64) if want_denom else None
+    rc = _load().es_oracle_spmm_backward(_ptr(rowptr, ctypes.c_int32), _ptr(colidx, ctypes.c_int32),
+                                         _ptr(vals_a, ctypes.c_float), _ptr(dY, ctypes.c_float),
+                                         ldy, N, int(F), int(W), _mode(mode), int(seed), _norm(norm),
+                                         _ptr(dX, ctypes.c_double), _ptr(D, ctypes.c_double))
+    if rc != 0:
+        raise ValueError("es_oracle_spmm_backward: bad argument")
+    return dX, D

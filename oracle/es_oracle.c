@@ -215,6 +215,48 @@ int es_oracle_spmm(const int32_t *rowptr, const int32_t *colidx, const float *va
     return 0;
 }
 
+/*
+ * Transposed product for the backward pass of a layer that used the sampled
+ * aggregation (Section 6.2 discusses training; the paper builds no backward
+ * kernel, so this is the plain definition of the adjoint of the forward
+ * operator above, with the same kept lists):
+ *     dX[c, :] = sum over rows r and kept slots i of r with colidx[kept_i] == c
+ *                of  f_r * vals[kept_i] * dY[r, :]
+ * f_r is the forward row factor.  dX and denom are [N x F] doubles, fully
+ * overwritten; denom accumulates f_r * |vals| * |dY|.  Rows are visited in
+ * order, slots in slot order.  Returns 0, or -1 on a bad argument.
+ */
+int es_oracle_spmm_backward(const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                            const float *dY, int64_t ldy, int64_t N, int64_t F, int64_t W,
+                            int32_t mode, uint64_t seed, int32_t norm, double *dX, double *denom)
+{
+    if (!rowptr || !dY || !dX || N < 0 || F < 1 || ldy < F || bad_mode(mode)) return -1;
+    if (norm < ORACLE_NORM_NONE || norm > ORACLE_NORM_RESCALE) return -1;
+    if (mode != ORACLE_FULL && W < 1) return -1;
+    if (!colidx && N > 0 && rowptr[N] > 0) return -1;
+    for (int64_t j = 0; j < N * F; ++j) dX[j] = 0.0;
+    if (denom) for (int64_t j = 0; j < N * F; ++j) denom[j] = 0.0;
+    for (int64_t r = 0; r < N; ++r) {
+        int64_t base = rowptr[r];
+        int64_t n = (int64_t)rowptr[r + 1] - base;
+        int64_t k = es_oracle_kept_count(mode, n, W);
+        double f = es_oracle_row_factor(norm, n, k);
+        const float *dy = dY + r * ldy;
+        for (int64_t i = 0; i < k; ++i) {
+            int64_t p = base + es_oracle_sample_index(mode, seed, r, i, n, W);
+            double a = f * (vals ? (double)vals[p] : 1.0);
+            int64_t c = colidx[p];
+            if (c < 0 || c >= N) return -1;
+            for (int64_t q = 0; q < F; ++q) dX[c * F + q] += a * (double)dy[q];
+            if (denom) {
+                double aa = fabs(a);
+                for (int64_t q = 0; q < F; ++q) denom[c * F + q] += aa * fabs((double)dy[q]);
+            }
+        }
+    }
+    return 0;
+}
+
 /* Threads the row loop of es_oracle_spmm uses. */
 int es_oracle_threads(void)
 {

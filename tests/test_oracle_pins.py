@@ -316,3 +316,41 @@ def test_normalisation_special_cases():
     assert (Yn == Yr).all() and (Dn == Dr).all()
     with pytest.raises(ValueError):
         oracle.spmm(w.rowptr, w.colidx, w.vals, w.X, w.F, 4, "bucket", 0, norm=9)
+
+
+# --------------------------------------------------------------------------
+# transposed product (backward pass of the sampled aggregation)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("norm", ["none", "mean", "rescale"])
+@pytest.mark.parametrize("mode,W", [("bucket", 3), ("fastrand", 3), ("full", 0), ("fastrand", 50)])
+def test_backward_vs_dense_transpose(mode, W, norm):
+    n, F = 41, 5
+    rowptr, colidx = random_csr(n, 7.0, seed=23, empty_frac=0.15)
+    rng = np.random.default_rng(5)
+    vals = rng.standard_normal(colidx.size).astype(np.float32)
+    dY = rng.standard_normal((n, F + 2)).astype(np.float32)        # ldy > F
+    pos, cnt = oracle.kept(rowptr, W, mode, 6)
+    A = _dense_from_kept(rowptr, colidx, vals, pos, cnt, n)
+    f = np.array([oracle.row_factor(norm, int(d), int(k)) for d, k in zip(np.diff(rowptr), cnt)])
+    A = f[:, None] * A
+    dX, D = oracle.spmm_backward(rowptr, colidx, vals, dY, F, W, mode, 6, norm=norm)
+    dYd = dY[:, :F].astype(np.float64)
+    np.testing.assert_allclose(dX, A.T @ dYd, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(D, np.abs(A).T @ np.abs(dYd), rtol=1e-13, atol=1e-13)
+
+
+def test_backward_is_the_adjoint_of_forward():
+    """<A_s X, dY> == <X, A_s^T dY> ties the backward oracle to the forward one."""
+    w = make_workload(2, scale=0.03)
+    rng = np.random.default_rng(9)
+    dY = rng.standard_normal((w.N, w.F)).astype(np.float32)
+    for mode, W, norm in (("fastrand", 8, "none"), ("bucket", 8, "mean"), ("full", 0, "rsqrt")):
+        Y, _ = oracle.spmm(w.rowptr, w.colidx, w.vals, w.X, w.F, W, mode, 2, norm=norm)
+        dX, _ = oracle.spmm_backward(w.rowptr, w.colidx, w.vals, dY, w.F, W, mode, 2, norm=norm)
+        lhs = float((Y * dY.astype(np.float64)).sum())
+        rhs = float((w.X.astype(np.float64) * dX).sum())
+        assert abs(lhs - rhs) <= 1e-10 * max(1.0, abs(lhs))
+    # full mode equals SciPy's transposed product
+    A = sp.csr_matrix((w.vals.astype(np.float64), w.colidx, w.rowptr), shape=(w.N, w.N))
+    dX, D = oracle.spmm_backward(w.rowptr, w.colidx, w.vals, dY, w.F, 0, "full")
+    np.testing.assert_allclose(dX, A.T @ dY.astype(np.float64), rtol=1e-12, atol=1e-12)
