@@ -284,6 +284,8 @@ def main() -> int:
                     log(f"  cfg3 {r['mode']:8s} W={r['W']:4d}: {r['ms']:.3f} ms  {r['eff_GBps']:.0f} GB/s  "
                         f"x{r['speedup_vs_full']} vs full")
                 extra.append(presampled_ablation(dw, dev))
+                extra.append(backward_table(dw, dev, ((("fastrand", 16), ("fastrand", 64), ("bucket", 64),
+                                                       ("fastrand", 256)))))
                 extra.append(gcn_feature_sweep(dw, dev, flush))
         result["extra"] = extra
     elif not args.no_cpu_baseline:
@@ -364,6 +366,28 @@ def presampled_ablation(dw, dev):
             log(f"  ablation {mode:8s} W={W:3d}: fused {t_fused:.3f} ms | materialise {t_mat:.3f} ms + "
                 f"full SpMM on pre-sampled {t_pre:.3f} ms")
             del orp, oci, ova
+    return out
+
+
+def backward_table(dw, dev, cases):
+    """es_spmm_backward (dX = sample_W(A)^T dY, fp32 atomic scatter) beside the
+    forward call of the same (mode, W).  Bytes counted: row pointers, sampled
+    (column, value) pairs, dY read once, dX zero-filled once, and one
+    read-modify-write of a dX row per kept entry."""
+    import torch
+    import paper_2104_10716_amd as es
+    dX = torch.empty_like(dw.Y)
+    out = {"workload": f"transposed product (backward) on the same graph, F={dw.F}", "rows": []}
+    for mode, W in cases:
+        kept = dw.nnz_kept(mode, W)
+        t_fwd = _time_fn(lambda: dw.launch(mode, W))
+        t_bwd = _time_fn(lambda: es.es_spmm_backward(dw.rowptr, dw.colidx, dw.vals, dw.X, dX, W, mode, 0,
+                                                     F=dw.F))
+        B = 4 * (dw.N + 1) + 8 * kept + 2 * 4 * dw.F * dw.N + 8 * dw.F * kept
+        out["rows"].append({"mode": mode, "W": W, "forward_ms": round(t_fwd, 4), "backward_ms": round(t_bwd, 4),
+                            "backward_GBps": round(B / (t_bwd * 1e6), 1)})
+        log(f"  backward {mode:8s} W={W:3d}: {t_bwd:.3f} ms ({B / (t_bwd * 1e6):.0f} GB/s incl. atomic RMW) "
+            f"vs forward {t_fwd:.3f} ms")
     return out
 
 

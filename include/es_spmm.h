@@ -102,6 +102,25 @@ int es_spmm_norm(const int32_t* rowptr, const int32_t* colidx, const float* vals
                  int32_t W, int32_t mode, uint64_t seed, int32_t norm, void* stream);
 
 /*
+ * es_spmm_backward -- the transposed product  dX = sample_W(A)^T * dY, i.e. the
+ * gradient of es_spmm_norm's output with respect to X for the same W, mode,
+ * seed and norm (training is the use Section 6.2 of the paper points to; the
+ * per-call seed gives a different edge subset per iteration).
+ *     dX[c, :] = sum over rows r and kept slots of r whose column is c
+ *                of  factor_r * vals[p] * dY[r, :]
+ *   dY  N rows of F fp32, row stride ldy >= F (input)
+ *   dX  N rows of F fp32, row stride ldx >= F (output, fully overwritten: the
+ *       library zero-fills it with a kernel of its own, then accumulates with
+ *       fp32 atomic adds, so the summation order -- and the last bits -- may
+ *       differ from launch to launch).  dX must not overlap dY.
+ * Every other argument as in es_spmm_norm.
+ */
+int es_spmm_backward(const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                     const float* dY, float* dX,
+                     int64_t N, int64_t nnz, int32_t F, int32_t ldy, int32_t ldx,
+                     int32_t W, int32_t mode, uint64_t seed, int32_t norm, void* stream);
+
+/*
  * es_spmm_sample_edges -- the sampler of Section 4.2 / 4.4 on its own, for
  * verification.  Runs the same device sampler and slot-to-lane schedule as
  * es_spmm and writes, for row r and slot i < k_r, the CSR position

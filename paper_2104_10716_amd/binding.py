@@ -46,6 +46,8 @@ def load_library():
     lib.es_spmm_norm.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
                                  ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                  ctypes.c_uint64, ctypes.c_int32, vp]
+    lib.es_spmm_backward.restype = ctypes.c_int
+    lib.es_spmm_backward.argtypes = lib.es_spmm_norm.argtypes
     lib.es_spmm_sample_edges.restype = ctypes.c_int
     lib.es_spmm_sample_edges.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                          ctypes.c_uint64, ctypes.c_int32, vp, vp, vp]
@@ -161,6 +163,19 @@ def es_spmm_norm(rowptr, colidx, vals, X, Y, W: int, mode, seed: int = 0, norm="
     if rc != 0:
         raise EsSpmmError(rc, "es_spmm_norm")
     return Y
+
+
+def es_spmm_backward(rowptr, colidx, vals, dY, dX, W: int, mode, seed: int = 0, norm="none",
+                     F: Optional[int] = None, stream=None, nnz: Optional[int] = None):
+    """dX[:, :F] = sample_W(A)^T @ dY[:, :F] (dX is overwritten); returns dX."""
+    lib = load_library()
+    args = _spmm_args(rowptr, colidx, vals, dY, dX, F, nnz)
+    nm = NORMS[norm] if isinstance(norm, str) else int(norm)
+    rc = lib.es_spmm_backward(*args, int(W), _mode(mode), int(seed) & 0xFFFFFFFFFFFFFFFF, nm,
+                              _stream_ptr(stream))
+    if rc != 0:
+        raise EsSpmmError(rc, "es_spmm_backward")
+    return dX
 
 
 def es_spmm_sample_edges(rowptr, W: int, mode, seed: int = 0, rows_per_wave: int = 0,

@@ -310,13 +310,51 @@ __device__ __forceinline__ float row_factor(int norm, int n, int k)
     return (float)n / (float)k;
 }
 
+// Transposed stage 2 (backward pass): every staged entry (c, v) of the tile adds
+// v * dy to row c of the output with fp32 atomics; edge slot e of E walks
+// entries e, e+E, ...  Atomics return nothing, so they pipeline by themselves.
+template <int G, int CH, int VEC, bool ALIGNED>
+__device__ __forceinline__ void scatter_tile(const uint2* tile, int count, int e, int E, float* out,
+                                             int64_t ldo, const LaneCols<G, CH, VEC, ALIGNED>& cols,
+                                             const Pack<VEC, ALIGNED> (&dy)[CH])
+{
+    for (int j = e; j < count; j += E) {
+        const uint2 ed = tile[j];
+        const float v = __uint_as_float(ed.y);
+        float* dst = out + (int64_t)ed.x * ldo;
+#pragma unroll
+        for (int ch = 0; ch < CH; ++ch) {
+            if (cols.ok[ch]) {
+                Pack<VEC, ALIGNED> t = dy[ch];
+                t.scale(v);
+                t.atomic_add(dst + cols.off[ch], cols.first[ch]);
+            }
+        }
+    }
+}
+
+// This lane's chunks of row r of the upstream gradient, times the row factor.
+template <int G, int CH, int VEC, bool ALIGNED>
+__device__ __forceinline__ void load_row_chunks(const Args& a, int64_t r, int n, int k,
+                                                const LaneCols<G, CH, VEC, ALIGNED>& cols,
+                                                Pack<VEC, ALIGNED> (&dy)[CH])
+{
+    const float f = row_factor(a.norm, n, k);
+    const float* src = a.X + r * (int64_t)a.ldx;
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) {
+        dy[ch].load(src + cols.off[ch]);
+        dy[ch].scale(f);
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Row part of the fused kernel (Algorithm 1) for workgroup `vb` of the row
 // grid.  G lanes x CH chunks x VEC floats cover one block of G*CH*VEC feature
 // columns (blockIdx.y selects the block).  Rows that keep more than long_k
 // entries are left to the long-row part and not stored here.
 // ---------------------------------------------------------------------------
-template <int G, int CH, int VEC, bool ALIGNED>
+template <int G, int CH, int VEC, bool ALIGNED, bool BACKWARD>
 __device__ __forceinline__ void row_block(const Args& a, uint32_t vb, uint2* lds)
 {
     constexpr int LOG_G = ilog2(G);
@@ -350,6 +388,20 @@ __device__ __forceinline__ void row_block(const Args& a, uint32_t vb, uint2* lds
 
     RowSampler sampler;
     sampler.init(a.mode, a.seed, r, (uint32_t)n, (uint32_t)a.W, (uint32_t)t, (uint32_t)team);
+
+    if (BACKWARD) {
+        // transposed product: a.X is the upstream gradient, a.Y the (zeroed) output
+        P dy[CH];
+        if (k > 0) load_row_chunks<G, CH, VEC, ALIGNED>(a, r, n, k_row, cols, dy);
+        for (int t0 = 0; t0 < k; t0 += T) {
+            const int count = min(k - t0, T);
+            stage_tile(sampler, t, team, count, base, a.colidx, a.vals, tile);
+            wave_lds_fence();
+            scatter_tile<G, CH, VEC, ALIGNED>(tile, count, e, E, a.Y, a.ldy, cols, dy);
+            wave_lds_fence();
+        }
+        return;
+    }
 
     P acc[CH];
 #pragma unroll
@@ -395,7 +447,7 @@ struct LongScratch {
     int wave_total[kWavesPerBlock];
 };
 
-template <int G, int CH, int VEC, bool ALIGNED>
+template <int G, int CH, int VEC, bool ALIGNED, bool BACKWARD>
 __device__ __forceinline__ void long_block(const Args& a, uint32_t bx, uint32_t by, uint2* lds,
                                            LongScratch& sc)
 {
@@ -468,6 +520,13 @@ __device__ __forceinline__ void long_block(const Args& a, uint32_t bx, uint32_t 
         sampler.init(a.mode, a.seed, r, (uint32_t)n, (uint32_t)a.W, (uint32_t)(t0 + lane), kWaveSize);
         stage_tile(sampler, lane, kWaveSize, count, base, a.colidx, a.vals, tile);
         wave_lds_fence();
+        if (BACKWARD) {
+            P dy[CH];
+            load_row_chunks<G, CH, VEC, ALIGNED>(a, r, n, k, cols, dy);
+            scatter_tile<G, CH, VEC, ALIGNED>(tile, count, e, E, a.Y, a.ldy, cols, dy);
+            wave_lds_fence();
+            continue;
+        }
         P acc[CH];
 #pragma unroll
         for (int ch = 0; ch < CH; ++ch) acc[ch].zero();
@@ -499,21 +558,34 @@ __device__ __forceinline__ void long_block(const Args& a, uint32_t bx, uint32_t 
 // workgroup b to XCD b % 8; long_blocks is a multiple of 8) walks one
 // contiguous range of rows.
 // ---------------------------------------------------------------------------
-template <int G, int CH, int VEC, bool ALIGNED>
+template <int G, int CH, int VEC, bool ALIGNED, bool BACKWARD>
 __global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
 {
     __shared__ uint2 lds[kWavesPerBlock * kWaveTileStride];
     __shared__ LongScratch long_scratch;
 
     if (blockIdx.x < a.long_blocks) {
-        long_block<G, CH, VEC, ALIGNED>(a, blockIdx.x / kLongSplit, blockIdx.x % kLongSplit, lds,
-                                        long_scratch);
+        long_block<G, CH, VEC, ALIGNED, BACKWARD>(a, blockIdx.x / kLongSplit, blockIdx.x % kLongSplit,
+                                                  lds, long_scratch);
         return;
     }
     const uint32_t b = blockIdx.x - a.long_blocks;
     const uint32_t vb = (b % kNumXcd) * a.blocks_per_xcd + b / kNumXcd;
     if (vb >= a.nblocks) return;
-    row_block<G, CH, VEC, ALIGNED>(a, vb, lds);
+    row_block<G, CH, VEC, ALIGNED, BACKWARD>(a, vb, lds);
+}
+
+// Zero-fills an [N x F] matrix with row stride ld (the transposed product
+// accumulates into its output with atomics).
+__global__ void __launch_bounds__(kBlockThreads)
+es_fill_zero_kernel(float* __restrict__ out, int64_t N, int32_t F, int32_t ld)
+{
+    const int64_t total = N * (int64_t)F;
+    for (int64_t i = (int64_t)blockIdx.x * kBlockThreads + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * kBlockThreads) {
+        const int64_t r = i / F;
+        out[r * ld + (i - r * F)] = 0.0f;
+    }
 }
 
 // Zeroes Y for the rows the long-row part will accumulate into with atomics.
@@ -736,7 +808,7 @@ int pick_logR(const Shape& s, double mean_kept)
 }
 
 template <int G, int CH, int VEC, bool ALIGNED>
-hipError_t launch(const Args& a, dim3 grid, hipStream_t st)
+hipError_t launch_forward(const Args& a, dim3 grid, hipStream_t st)
 {
     if (a.long_blocks > 0) {
         const uint32_t zb = (uint32_t)((a.N + kBlockThreads - 1) / kBlockThreads);
@@ -744,7 +816,25 @@ hipError_t launch(const Args& a, dim3 grid, hipStream_t st)
         const hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
-    hipLaunchKernelGGL((es_spmm_kernel<G, CH, VEC, ALIGNED>), grid, dim3(kBlockThreads), 0, st, a);
+    hipLaunchKernelGGL((es_spmm_kernel<G, CH, VEC, ALIGNED, false>), grid, dim3(kBlockThreads), 0, st, a);
+    return hipGetLastError();
+}
+
+// The transposed product always runs the 32-bit interleaved column mapping
+// (lane l owns columns l, l+G, ...): one atomic instruction then covers G
+// consecutive floats of an output row instead of every fourth one, which is
+// what the memory-side atomic units are fastest at (measured 4x over the
+// 128-bit mapping); G is as wide as F allows for the same reason.
+template <int G, int CH>
+hipError_t launch_backward(const Args& a, dim3 grid, hipStream_t st)
+{
+    int64_t fb = (a.N * (int64_t)a.F + kBlockThreads * 8 - 1) / (kBlockThreads * 8);
+    if (fb > 65536) fb = 65536;
+    hipLaunchKernelGGL(es_fill_zero_kernel, dim3((uint32_t)fb), dim3(kBlockThreads), 0, st, a.Y, a.N, a.F,
+                       a.ldy);
+    const hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL((es_spmm_kernel<G, CH, 1, false, true>), grid, dim3(kBlockThreads), 0, st, a);
     return hipGetLastError();
 }
 
@@ -760,6 +850,10 @@ int32_t pick_long_k(const Shape& s, int logR, double entries, int F)
     const int32_t v = ((int32_t)k / kLongMin) * kLongMin;
     return v < kLongMin ? kLongMin : v;
 }
+
+int es_run(const int32_t* rowptr, const int32_t* colidx, const float* vals, const float* X, float* Y,
+           int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W, int32_t mode,
+           uint64_t seed, int32_t norm, bool backward, void* stream);
 
 int32_t g_force_logR = -1;   // es_spmm_set_rows_per_wave override; -1 = heuristic
 int32_t g_force_long_k = 0;  // es_spmm_set_long_row_threshold override; 0 = heuristic
@@ -818,6 +912,25 @@ int es_spmm_norm(const int32_t* rowptr, const int32_t* colidx, const float* vals
                  float* Y, int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W,
                  int32_t mode, uint64_t seed, int32_t norm, void* stream)
 {
+    return es_run(rowptr, colidx, vals, X, Y, N, nnz, F, ldx, ldy, W, mode, seed, norm, false, stream);
+}
+
+int es_spmm_backward(const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                     const float* dY, float* dX, int64_t N, int64_t nnz, int32_t F, int32_t ldy,
+                     int32_t ldx, int32_t W, int32_t mode, uint64_t seed, int32_t norm, void* stream)
+{
+    return es_run(rowptr, colidx, vals, dY, dX, N, nnz, F, ldy, ldx, W, mode, seed, norm, true, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+// Shared host path of es_spmm_norm (X -> Y) and es_spmm_backward (dY -> dX).
+int es_run(const int32_t* rowptr, const int32_t* colidx, const float* vals, const float* X, float* Y,
+           int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W, int32_t mode,
+           uint64_t seed, int32_t norm, bool backward, void* stream)
+{
     if (norm < ES_NORM_NONE || norm > ES_NORM_RESCALE) return ES_ERR_INVALID_ARG;
     if (N < 0 || nnz < 0 || nnz > INT32_MAX || F < 1 || ldx < F || ldy < F) return ES_ERR_INVALID_ARG;
     if (mode != ES_FULL && mode != ES_BUCKET && mode != ES_FASTRAND) return ES_ERR_INVALID_ARG;
@@ -831,7 +944,14 @@ int es_spmm_norm(const int32_t* rowptr, const int32_t* colidx, const float* vals
                          (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
     if (reinterpret_cast<uintptr_t>(X) % 4 || reinterpret_cast<uintptr_t>(Y) % 4)
         return ES_ERR_INVALID_ARG;
-    const Shape s = pick_shape(F, aligned);
+    Shape s = pick_shape(F, aligned);
+    if (backward) {                                        // see launch_backward
+        s.vec = 1; s.aligned = false;
+        s.G = next_pow2(F);
+        if (s.G < 4) s.G = 4;
+        if (s.G > 64) s.G = 64;
+        s.CH = F > 128 ? 4 : F > 64 ? 2 : 1;
+    }
 
     double mean = (double)nnz / (double)N;
     if (mode != ES_FULL && mean > (double)W) mean = (double)W;
@@ -875,16 +995,24 @@ int es_spmm_norm(const int32_t* rowptr, const int32_t* colidx, const float* vals
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t err = hipErrorInvalidValue;
 #define ES_CASE(G_, CH_, V_, A_)                                                   \
-    if (s.G == G_ && s.CH == CH_ && s.vec == V_ && s.aligned == A_)                \
-        err = launch<G_, CH_, V_, A_>(a, grid, st);
+    if (!backward && s.G == G_ && s.CH == CH_ && s.vec == V_ && s.aligned == A_)   \
+        err = launch_forward<G_, CH_, V_, A_>(a, grid, st);
     ES_CASE(4, 1, 4, true) ES_CASE(8, 1, 4, true) ES_CASE(16, 1, 4, true) ES_CASE(32, 1, 4, true)
     ES_CASE(64, 1, 4, true) ES_CASE(64, 2, 4, true) ES_CASE(64, 4, 4, true)
     ES_CASE(4, 1, 4, false) ES_CASE(8, 1, 4, false) ES_CASE(16, 1, 4, false) ES_CASE(32, 1, 4, false)
     ES_CASE(64, 1, 4, false) ES_CASE(64, 2, 4, false) ES_CASE(64, 4, 4, false)
     ES_CASE(4, 1, 1, false)
+#define ES_BWD(G_, CH_) \
+    if (backward && s.G == G_ && s.CH == CH_) err = launch_backward<G_, CH_>(a, grid, st);
+    ES_BWD(4, 1) ES_BWD(8, 1) ES_BWD(16, 1) ES_BWD(32, 1) ES_BWD(64, 1) ES_BWD(64, 2) ES_BWD(64, 4)
+#undef ES_BWD
 #undef ES_CASE
     return err == hipSuccess ? ES_OK : ES_ERR_LAUNCH;
 }
+
+}  // namespace
+
+extern "C" {
 
 int es_spmm_materialize(const int32_t* rowptr, const int32_t* colidx, const float* vals, int64_t N,
                         int64_t nnz, int32_t W, int32_t mode, uint64_t seed, int32_t* out_rowptr,

@@ -74,3 +74,16 @@ def check_edges(d, W, mode, seed=0, rows_per_wave=0, what=""):
     what = what or f"{mode} W={W} seed={seed} rpw={rows_per_wave}"
     assert np.array_equal(cnt.cpu().numpy(), ocnt), f"{what}: kept counts differ"
     assert np.array_equal(pos.cpu().numpy(), opos), f"{what}: sampled edge lists differ"
+
+
+def check_backward_against_oracle(d, W, mode, seed=0, norm="none", what=""):
+    """es_spmm_backward on DeviceCSR `d` (its X plays the upstream gradient dY)
+    against the oracle's transposed product, every element."""
+    import torch
+    import oracle
+    import paper_2104_10716_amd as es
+    dX = torch.full((d.N, d.F), float("nan"), dtype=torch.float32, device=d.X.device)
+    es.es_spmm_backward(d.rowptr, d.colidx, d.vals, d.X, dX, W, mode, seed, norm, F=d.F)
+    torch.cuda.synchronize()
+    ref, den = oracle.spmm_backward(d.h_rowptr, d.h_colidx, d.h_vals, d.h_X, d.F, W, mode, seed, norm=norm)
+    return check_Y(dX.cpu().numpy(), ref, den, what or f"backward {mode} W={W} seed={seed} norm={norm}")

@@ -190,6 +190,55 @@ def test_in_kernel_normalisation(es, norm):
         d.run(4, "bucket", norm=7)
 
 
+@pytest.mark.parametrize("F,ldx", [(3, 3), (16, 16), (41, 41), (64, 68), (100, 128), (256, 256), (520, 520)])
+def test_backward_small_graphs(es, F, ldx):
+    """es_spmm_backward (transposed sampled product) against the oracle on
+    ragged small graphs: every mode, row factor, launch shape and the long-row path."""
+    from gpu_util import DeviceCSR, check_backward_against_oracle
+    rowptr, colidx, vals, dY = _random_graph(650, 12.0, seed=100 + F, F=F, ldx=ldx)
+    d = DeviceCSR(rowptr, colidx, vals, dY, F=F)
+    maxdeg = int(np.diff(rowptr).max())
+    for rpw in (0, 1, 8):
+        es.es_spmm_set_rows_per_wave(rpw)
+        for thr in (0, 5):
+            es.es_spmm_set_long_row_threshold(thr)
+            for mode, W in (("full", 0), ("bucket", 4), ("fastrand", 4), ("fastrand", maxdeg - 1),
+                            ("fastrand", maxdeg + 3)):
+                for norm in ("none", "mean", "rescale"):
+                    check_backward_against_oracle(d, W, mode, 31, norm,
+                                                  what=f"backward F={F} {mode} W={W} {norm} rpw={rpw} thr={thr}")
+    es.es_spmm_set_rows_per_wave(0)
+    es.es_spmm_set_long_row_threshold(0)
+    du = DeviceCSR(rowptr, colidx, None, dY, F=F)              # unweighted
+    check_backward_against_oracle(du, 4, "fastrand", 1, what=f"backward unit values F={F}")
+
+
+def test_backward_full_size(es):
+    """Transposed product on configs 2 and 3 at full size, every element
+    against the oracle; and the adjoint identity <A_s X, dY> = <X, A_s^T dY>
+    between the two HIP entry points."""
+    import torch
+    from gpu_util import DeviceCSR, check_backward_against_oracle
+    for cfg, cases in ((2, (("fastrand", 16), ("bucket", 128), ("full", 0))), (3, (("fastrand", 64), ("bucket", 16)))):
+        w = _workload(cfg)
+        dY = np.random.default_rng(cfg).standard_normal((w.N, w.F)).astype(np.float32)
+        d = DeviceCSR(w.rowptr, w.colidx, w.vals, dY)
+        for mode, W in cases:
+            worst = check_backward_against_oracle(d, W, mode, 0, what=f"cfg{cfg} backward {mode} W={W}")
+            _say(f"cfg{cfg} backward {mode} W={W}: max normalised error {worst:.2e}")
+        Xd = torch.from_numpy(w.X).to("cuda:0")
+        Y = torch.empty((w.N, w.F), dtype=torch.float32, device="cuda:0")
+        dX = torch.empty_like(Y)
+        es.es_spmm_norm(d.rowptr, d.colidx, d.vals, Xd, Y, 32, "fastrand", 7, "mean")
+        es.es_spmm_backward(d.rowptr, d.colidx, d.vals, d.X, dX, 32, "fastrand", 7, "mean")
+        lhs = (Y.double() * d.X.double()).sum().item()
+        rhs = (Xd.double() * dX.double()).sum().item()
+        scale = (Y.double().abs() * d.X.double().abs()).sum().item()
+        assert abs(lhs - rhs) <= 1e-5 * scale, (cfg, lhs, rhs)
+        _say(f"cfg{cfg}: adjoint identity holds, |lhs-rhs|/scale = {abs(lhs - rhs) / scale:.2e}")
+        del d, Xd, Y, dX
+
+
 def test_hip_graph_capture_and_replay(es):
     """es_spmm only enqueues kernels, so a caller can capture it in a HIP graph.
     Replays (with eager work and synchronisations in between) must reproduce the
