@@ -153,6 +153,32 @@ int es_spmm_materialize(const int32_t* rowptr, const int32_t* colidx, const floa
                         int32_t* out_rowptr, int32_t* out_colidx, float* out_vals,
                         void* stream);
 
+/*
+ * es_spmm_launch_info -- the launch shape es_spmm_norm (backward == 0) or
+ * es_spmm_backward (backward != 0) would pick for these sizes, without
+ * launching anything and without a GPU.  `aligned16`: both matrices are
+ * 16-byte aligned.  The shape is how Section 4.5's "thread management" maps
+ * onto wave64: lanes_per_row x edge_slots lanes form a row's thread group,
+ * rows_per_wave such groups share a wavefront.  Honours the two overrides
+ * below.  N must be >= 1.
+ */
+typedef struct {
+    int32_t vector_width;        /* floats per load: 4 (128-bit) or 1              */
+    int32_t aligned;             /* 1: rows are 16-byte aligned                     */
+    int32_t lanes_per_row;       /* G: lanes spanning the feature columns           */
+    int32_t chunks_per_lane;     /* CH: column chunks each of those lanes owns      */
+    int32_t rows_per_wave;       /* R                                               */
+    int32_t edge_slots;          /* E = 64 / (R * G): entries of a row in flight    */
+    int32_t loads_in_flight;     /* U: independent loads per lane before the FMAs   */
+    int32_t tile_slots_per_row;  /* LDS (column, value) slots per row and refill    */
+    int32_t long_row_threshold;  /* rows keeping more entries are split             */
+    int64_t long_row_workgroups; /* leading workgroups that serve such rows (or 0)  */
+    int64_t grid_x, grid_y;      /* launch grid, 256 threads per workgroup          */
+} es_launch_info_t;
+
+int es_spmm_launch_info(int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W,
+                        int32_t mode, int32_t aligned16, int32_t backward, es_launch_info_t* info);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* es_spmm_status_string(int status);
 

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     EsSpmmError,
     es_spmm,
     es_spmm_backward,
+    es_spmm_launch_info,
     es_spmm_materialize,
     es_spmm_max_W,
     es_spmm_norm,

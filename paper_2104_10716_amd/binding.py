@@ -11,6 +11,17 @@ MODES = {"full": ES_FULL, "bucket": ES_BUCKET, "fastrand": ES_FASTRAND}
 ES_NORM_NONE, ES_NORM_MEAN, ES_NORM_RSQRT, ES_NORM_RESCALE = 0, 1, 2, 3
 NORMS = {"none": ES_NORM_NONE, "mean": ES_NORM_MEAN, "rsqrt": ES_NORM_RSQRT, "rescale": ES_NORM_RESCALE}
 
+
+
+class es_launch_info_t(ctypes.Structure):
+    _fields_ = [("vector_width", ctypes.c_int32), ("aligned", ctypes.c_int32),
+                ("lanes_per_row", ctypes.c_int32), ("chunks_per_lane", ctypes.c_int32),
+                ("rows_per_wave", ctypes.c_int32), ("edge_slots", ctypes.c_int32),
+                ("loads_in_flight", ctypes.c_int32), ("tile_slots_per_row", ctypes.c_int32),
+                ("long_row_threshold", ctypes.c_int32), ("long_row_workgroups", ctypes.c_int64),
+                ("grid_x", ctypes.c_int64), ("grid_y", ctypes.c_int64)]
+
+
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libes_spmm.so")
 _lib = None
@@ -54,6 +65,10 @@ def load_library():
     lib.es_spmm_materialize.restype = ctypes.c_int
     lib.es_spmm_materialize.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
                                         ctypes.c_int32, ctypes.c_uint64, vp, vp, vp, vp]
+    lib.es_spmm_launch_info.restype = ctypes.c_int
+    lib.es_spmm_launch_info.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                        ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                        ctypes.c_int32, ctypes.POINTER(es_launch_info_t)]
     lib.es_spmm_status_string.restype = ctypes.c_char_p
     lib.es_spmm_status_string.argtypes = [ctypes.c_int]
     lib.es_spmm_max_W.restype = ctypes.c_int32
@@ -228,3 +243,15 @@ def es_spmm_materialize(rowptr, colidx, vals, W: int, mode, seed: int = 0, out_r
     if rc != 0:
         raise EsSpmmError(rc, "es_spmm_materialize")
     return out_rowptr, out_colidx, out_vals
+
+
+def es_spmm_launch_info(N: int, nnz: int, F: int, W: int, mode, ldx: Optional[int] = None,
+                        ldy: Optional[int] = None, aligned16: bool = True, backward: bool = False) -> dict:
+    """Launch shape the library would pick (host-only; needs no GPU)."""
+    info = es_launch_info_t()
+    rc = load_library().es_spmm_launch_info(int(N), int(nnz), int(F), int(F if ldx is None else ldx),
+                                            int(F if ldy is None else ldy), int(W), _mode(mode),
+                                            int(bool(aligned16)), int(bool(backward)), ctypes.byref(info))
+    if rc != 0:
+        raise EsSpmmError(rc, "es_spmm_launch_info")
+    return {name: int(getattr(info, name)) for name, _ in es_launch_info_t._fields_}

@@ -851,12 +851,122 @@ int32_t pick_long_k(const Shape& s, int logR, double entries, int F)
     return v < kLongMin ? kLongMin : v;
 }
 
-int es_run(const int32_t* rowptr, const int32_t* colidx, const float* vals, const float* X, float* Y,
-           int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W, int32_t mode,
-           uint64_t seed, int32_t norm, bool backward, void* stream);
-
 int32_t g_force_logR = -1;   // es_spmm_set_rows_per_wave override; -1 = heuristic
 int32_t g_force_long_k = 0;  // es_spmm_set_long_row_threshold override; 0 = heuristic
+
+// Everything the host decides about one launch.
+struct Plan {
+    Shape s;
+    int logR;                  // log2(rows per wave)
+    int32_t long_k;            // long-row threshold
+    int64_t nblocks;           // row workgroups that carry rows
+    int64_t per_xcd;           // row workgroups per XCD
+    int64_t grid_x, grid_y;    // launch grid (long-row workgroups included in grid_x)
+    int64_t long_blocks;       // leading long-row workgroups
+};
+
+int check_sizes(int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W, int32_t mode,
+                int32_t norm)
+{
+    if (norm < ES_NORM_NONE || norm > ES_NORM_RESCALE) return ES_ERR_INVALID_ARG;
+    if (N < 0 || nnz < 0 || nnz > INT32_MAX || F < 1 || ldx < F || ldy < F) return ES_ERR_INVALID_ARG;
+    if (mode != ES_FULL && mode != ES_BUCKET && mode != ES_FASTRAND) return ES_ERR_INVALID_ARG;
+    if (mode != ES_FULL && W < 1) return ES_ERR_INVALID_ARG;
+    return ES_OK;
+}
+
+// Launch shape for N >= 1 rows.  `aligned`: F and both row strides are
+// multiples of 4 and both matrices are 16-byte aligned.
+int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool aligned, bool backward,
+              Plan* p)
+{
+    Shape s = pick_shape(F, aligned);
+    if (backward) {                                        // see launch_backward
+        s.vec = 1; s.aligned = false;
+        s.G = next_pow2(F);
+        if (s.G < 4) s.G = 4;
+        if (s.G > 64) s.G = 64;
+        s.CH = F > 128 ? 4 : F > 64 ? 2 : 1;
+    }
+    p->s = s;
+
+    double mean = (double)nnz / (double)N;
+    if (mode != ES_FULL && mean > (double)W) mean = (double)W;
+    int logR = pick_logR(s, mean);
+    if (g_force_logR >= 0) {
+        logR = g_force_logR;
+        while ((64 >> logR) < s.G) --logR;                 // at least one edge slot per row
+    }
+    p->logR = logR;
+
+    const int64_t rows_per_block = (int64_t)kWavesPerBlock << logR;
+    p->nblocks = (N + rows_per_block - 1) / rows_per_block;
+    p->per_xcd = (p->nblocks + kNumXcd - 1) / kNumXcd;
+    const int cols_per_block = s.G * s.CH * s.vec;
+    p->grid_y = ((int64_t)F + cols_per_block - 1) / cols_per_block;
+
+    // rows that may keep more than long_k entries exist only in full mode or
+    // for W above the bound (nnz is a hint, so it does not gate the launch)
+    double entries = (double)nnz;
+    if (mode != ES_FULL && entries > (double)N * W) entries = (double)N * W;
+    p->long_k = pick_long_k(s, logR, entries, F);
+    // the long-row part costs a second small launch and a scan of the row
+    // pointers; below one tile per row that is more than the tail it removes
+    if (mode != ES_FULL && p->long_k < kTileSlots) p->long_k = kTileSlots;
+    if (g_force_long_k > 0) p->long_k = g_force_long_k;
+    const bool may_be_long = mode == ES_FULL || W > p->long_k;
+    p->long_blocks = may_be_long ? ((N + kLongScanRows - 1) / kLongScanRows) * kLongSplit : 0;
+    p->grid_x = p->per_xcd * kNumXcd + p->long_blocks;
+    if (p->grid_x > INT32_MAX || p->grid_y > 65535) return ES_ERR_UNSUPPORTED;
+    return ES_OK;
+}
+
+// Shared host path of es_spmm_norm (X -> Y) and es_spmm_backward (dY -> dX).
+int es_run(const int32_t* rowptr, const int32_t* colidx, const float* vals, const float* X, float* Y,
+           int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W, int32_t mode,
+           uint64_t seed, int32_t norm, bool backward, void* stream)
+{
+    const int bad = check_sizes(N, nnz, F, ldx, ldy, W, mode, norm);
+    if (bad != ES_OK) return bad;
+    if (N == 0) return ES_OK;
+    if (!rowptr || !X || !Y) return ES_ERR_INVALID_ARG;
+    if (nnz > 0 && !colidx) return ES_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(X) % 4 || reinterpret_cast<uintptr_t>(Y) % 4)
+        return ES_ERR_INVALID_ARG;
+    const bool aligned = (F % 4 == 0) && (ldx % 4 == 0) && (ldy % 4 == 0) &&
+                         (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
+                         (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
+    Plan p;
+    const int rc = make_plan(N, nnz, F, W, mode, aligned, backward, &p);
+    if (rc != ES_OK) return rc;
+    const Shape& s = p.s;
+
+    Args a;
+    a.rowptr = rowptr; a.colidx = colidx; a.vals = vals; a.X = X; a.Y = Y;
+    a.N = N; a.seed = seed; a.F = F; a.ldx = ldx; a.ldy = ldy;
+    a.W = (mode == ES_FULL) ? INT32_MAX : W;
+    a.mode = mode; a.logR = p.logR; a.norm = norm; a.long_k = p.long_k;
+    a.nblocks = (uint32_t)p.nblocks; a.blocks_per_xcd = (uint32_t)p.per_xcd;
+    a.long_blocks = (uint32_t)p.long_blocks;
+
+    const dim3 grid((uint32_t)p.grid_x, (uint32_t)p.grid_y);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t err = hipErrorInvalidValue;
+#define ES_CASE(G_, CH_, V_, A_)                                                   \
+    if (!backward && s.G == G_ && s.CH == CH_ && s.vec == V_ && s.aligned == A_)   \
+        err = launch_forward<G_, CH_, V_, A_>(a, grid, st);
+    ES_CASE(4, 1, 4, true) ES_CASE(8, 1, 4, true) ES_CASE(16, 1, 4, true) ES_CASE(32, 1, 4, true)
+    ES_CASE(64, 1, 4, true) ES_CASE(64, 2, 4, true) ES_CASE(64, 4, 4, true)
+    ES_CASE(4, 1, 4, false) ES_CASE(8, 1, 4, false) ES_CASE(16, 1, 4, false) ES_CASE(32, 1, 4, false)
+    ES_CASE(64, 1, 4, false) ES_CASE(64, 2, 4, false) ES_CASE(64, 4, 4, false)
+    ES_CASE(4, 1, 1, false)
+#define ES_BWD(G_, CH_) \
+    if (backward && s.G == G_ && s.CH == CH_) err = launch_backward<G_, CH_>(a, grid, st);
+    ES_BWD(4, 1) ES_BWD(8, 1) ES_BWD(16, 1) ES_BWD(32, 1) ES_BWD(64, 1) ES_BWD(64, 2) ES_BWD(64, 4)
+#undef ES_BWD
+#undef ES_CASE
+    return err == hipSuccess ? ES_OK : ES_ERR_LAUNCH;
+}
 
 }  // namespace
 
@@ -922,97 +1032,31 @@ int es_spmm_backward(const int32_t* rowptr, const int32_t* colidx, const float* 
     return es_run(rowptr, colidx, vals, dY, dX, N, nnz, F, ldy, ldx, W, mode, seed, norm, true, stream);
 }
 
-}  // extern "C"
-
-namespace {
-
-// Shared host path of es_spmm_norm (X -> Y) and es_spmm_backward (dY -> dX).
-int es_run(const int32_t* rowptr, const int32_t* colidx, const float* vals, const float* X, float* Y,
-           int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W, int32_t mode,
-           uint64_t seed, int32_t norm, bool backward, void* stream)
+int es_spmm_launch_info(int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W,
+                        int32_t mode, int32_t aligned16, int32_t backward, es_launch_info_t* info)
 {
-    if (norm < ES_NORM_NONE || norm > ES_NORM_RESCALE) return ES_ERR_INVALID_ARG;
-    if (N < 0 || nnz < 0 || nnz > INT32_MAX || F < 1 || ldx < F || ldy < F) return ES_ERR_INVALID_ARG;
-    if (mode != ES_FULL && mode != ES_BUCKET && mode != ES_FASTRAND) return ES_ERR_INVALID_ARG;
-    if (mode != ES_FULL && W < 1) return ES_ERR_INVALID_ARG;
-    if (N == 0) return ES_OK;
-    if (!rowptr || !X || !Y) return ES_ERR_INVALID_ARG;
-    if (nnz > 0 && !colidx) return ES_ERR_INVALID_ARG;
-
-    const bool aligned = (F % 4 == 0) && (ldx % 4 == 0) && (ldy % 4 == 0) &&
-                         (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
-                         (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
-    if (reinterpret_cast<uintptr_t>(X) % 4 || reinterpret_cast<uintptr_t>(Y) % 4)
-        return ES_ERR_INVALID_ARG;
-    Shape s = pick_shape(F, aligned);
-    if (backward) {                                        // see launch_backward
-        s.vec = 1; s.aligned = false;
-        s.G = next_pow2(F);
-        if (s.G < 4) s.G = 4;
-        if (s.G > 64) s.G = 64;
-        s.CH = F > 128 ? 4 : F > 64 ? 2 : 1;
-    }
-
-    double mean = (double)nnz / (double)N;
-    if (mode != ES_FULL && mean > (double)W) mean = (double)W;
-    int logR = pick_logR(s, mean);
-    if (g_force_logR >= 0) {
-        logR = g_force_logR;
-        while ((64 >> logR) < s.G) --logR;                 // at least one edge slot per row
-    }
-
-    const int64_t rows_per_block = (int64_t)kWavesPerBlock << logR;
-    const int64_t nblocks = (N + rows_per_block - 1) / rows_per_block;
-    const int64_t per_xcd = (nblocks + kNumXcd - 1) / kNumXcd;
-    const int64_t grid_x = per_xcd * kNumXcd;
-    const int cols_per_block = s.G * s.CH * s.vec;
-    const int64_t grid_y = ((int64_t)F + cols_per_block - 1) / cols_per_block;
-    if (grid_x > INT32_MAX || grid_y > 65535) return ES_ERR_UNSUPPORTED;
-
-    Args a;
-    a.rowptr = rowptr; a.colidx = colidx; a.vals = vals; a.X = X; a.Y = Y;
-    a.N = N; a.seed = seed; a.F = F; a.ldx = ldx; a.ldy = ldy;
-    a.W = (mode == ES_FULL) ? INT32_MAX : W;
-    a.mode = mode; a.logR = logR; a.norm = norm;
-    a.nblocks = (uint32_t)nblocks; a.blocks_per_xcd = (uint32_t)per_xcd;
-
-    // rows that may keep more than long_k entries exist only in full mode or
-    // for W above the bound (nnz is a hint, so it does not gate the launch)
-    double entries = (double)nnz;
-    if (mode != ES_FULL && entries > (double)N * W) entries = (double)N * W;
-    a.long_k = pick_long_k(s, logR, entries, F);
-    // the long-row part costs a second small launch and a scan of the row
-    // pointers; below one tile per row that is more than the tail it removes
-    if (mode != ES_FULL && a.long_k < kTileSlots) a.long_k = kTileSlots;
-    if (g_force_long_k > 0) a.long_k = g_force_long_k;
-    const bool may_be_long = mode == ES_FULL || W > a.long_k;
-    const int64_t long_blocks =
-        may_be_long ? ((N + kLongScanRows - 1) / kLongScanRows) * kLongSplit : 0;
-    if (grid_x + long_blocks > INT32_MAX) return ES_ERR_UNSUPPORTED;
-    a.long_blocks = (uint32_t)long_blocks;
-
-    const dim3 grid((uint32_t)(grid_x + long_blocks), (uint32_t)grid_y);
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t err = hipErrorInvalidValue;
-#define ES_CASE(G_, CH_, V_, A_)                                                   \
-    if (!backward && s.G == G_ && s.CH == CH_ && s.vec == V_ && s.aligned == A_)   \
-        err = launch_forward<G_, CH_, V_, A_>(a, grid, st);
-    ES_CASE(4, 1, 4, true) ES_CASE(8, 1, 4, true) ES_CASE(16, 1, 4, true) ES_CASE(32, 1, 4, true)
-    ES_CASE(64, 1, 4, true) ES_CASE(64, 2, 4, true) ES_CASE(64, 4, 4, true)
-    ES_CASE(4, 1, 4, false) ES_CASE(8, 1, 4, false) ES_CASE(16, 1, 4, false) ES_CASE(32, 1, 4, false)
-    ES_CASE(64, 1, 4, false) ES_CASE(64, 2, 4, false) ES_CASE(64, 4, 4, false)
-    ES_CASE(4, 1, 1, false)
-#define ES_BWD(G_, CH_) \
-    if (backward && s.G == G_ && s.CH == CH_) err = launch_backward<G_, CH_>(a, grid, st);
-    ES_BWD(4, 1) ES_BWD(8, 1) ES_BWD(16, 1) ES_BWD(32, 1) ES_BWD(64, 1) ES_BWD(64, 2) ES_BWD(64, 4)
-#undef ES_BWD
-#undef ES_CASE
-    return err == hipSuccess ? ES_OK : ES_ERR_LAUNCH;
+    if (!info) return ES_ERR_INVALID_ARG;
+    const int bad = check_sizes(N, nnz, F, ldx, ldy, W, mode, ES_NORM_NONE);
+    if (bad != ES_OK) return bad;
+    if (N == 0) return ES_ERR_INVALID_ARG;
+    const bool aligned = aligned16 && (F % 4 == 0) && (ldx % 4 == 0) && (ldy % 4 == 0);
+    Plan p;
+    const int rc = make_plan(N, nnz, F, W, mode, aligned, backward != 0, &p);
+    if (rc != ES_OK) return rc;
+    info->vector_width = p.s.vec;
+    info->aligned = p.s.aligned ? 1 : 0;
+    info->lanes_per_row = p.s.G;
+    info->chunks_per_lane = p.s.CH;
+    info->rows_per_wave = 1 << p.logR;
+    info->edge_slots = (64 >> p.logR) / p.s.G;
+    info->loads_in_flight = 8 / p.s.CH;
+    info->tile_slots_per_row = kTileSlots >> p.logR;
+    info->long_row_threshold = p.long_k;
+    info->long_row_workgroups = p.long_blocks;
+    info->grid_x = p.grid_x;
+    info->grid_y = p.grid_y;
+    return ES_OK;
 }
-
-}  // namespace
-
-extern "C" {
 
 int es_spmm_materialize(const int32_t* rowptr, const int32_t* colidx, const float* vals, int64_t N,
                         int64_t nnz, int32_t W, int32_t mode, uint64_t seed, int32_t* out_rowptr,
