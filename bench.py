@@ -169,8 +169,8 @@ def cpu_baseline_rows(dw, calls, target_seconds=20.0):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, choices=(2, 3, 4))
     ap.add_argument("--main-only", action="store_true",
                     help="only the timed sweep of --config (what the rocprofv3 summaries profile)")
