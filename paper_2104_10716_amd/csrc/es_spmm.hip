@@ -55,7 +55,7 @@ struct Args {
     int64_t N;
     uint64_t seed;
     int32_t F, ldx, ldy, W, mode, logR;
-    int32_t long_k;            // rows keeping more entries go to the long-row kernel
+    int32_t long_k;            // rows keeping more entries go to the long-row part  
     int32_t norm;              // es_norm_t: row factor applied before the store
     uint32_t nblocks;          // workgroups that carry rows
     uint32_t blocks_per_xcd;   // ceil(nblocks / 8)
