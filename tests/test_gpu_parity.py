@@ -474,6 +474,59 @@ def test_full_size_every_row_counts_its_kept_entries(es, cfg):
         _say(f"cfg{cfg} fastrand W=4: column-id sums exact on {int(ok.sum())} of {w.N} rows")
 
 
+def test_maximum_sizes_int32_index_range(es):
+    """nnz just below 2^31 (the int32 CSR limit) and N*W just below 2^31 for the
+    sampler export: 4 Mi rows of 511 entries.  The graph is drawn on the device
+    (torch, seeded) because 2.1 G entries are too many to push through the host;
+    checks: every row's exact kept count, and the oracle on sampled rows whose
+    entries are copied back."""
+    import torch
+    import oracle
+    from gpu_util import check_Y
+    dev = "cuda:0"
+    N, deg, F = 1 << 22, 511, 4
+    nnz = N * deg
+    assert nnz < 2 ** 31 and nnz > 2 ** 31 - 2 ** 23
+    g = torch.Generator(device=dev)
+    g.manual_seed(1234)
+    colidx = torch.randint(0, N, (nnz,), dtype=torch.int32, device=dev, generator=g)
+    rowptr = (torch.arange(N + 1, dtype=torch.int64, device=dev) * deg).to(torch.int32)
+    ones = torch.ones((N, F), dtype=torch.float32, device=dev)
+    Y = torch.empty((N, F), dtype=torch.float32, device=dev)
+    for mode, W in (("fastrand", 16), ("bucket", 500), ("full", 0)):
+        Y.fill_(float("nan"))
+        es.es_spmm(rowptr, colidx, None, ones, Y, W, mode, 0)
+        torch.cuda.synchronize()
+        expect = float(deg if mode == "full" else min(deg, W))
+        assert bool((Y == expect).all()), f"max size {mode} W={W}"
+        _say(f"max size nnz={nnz}: {mode} W={W} counts exact on all {N} rows")
+    # oracle on sampled rows (last rows included: their entries sit at the top of the index range)
+    rows = np.unique(np.concatenate([np.random.default_rng(0).integers(0, N, 300),
+                                     [0, N - 1, N - 2, N // 2]])).astype(np.int64)
+    sub_cols = np.stack([colidx[r * deg:(r + 1) * deg].cpu().numpy() for r in rows])
+    sub_rowptr = (np.arange(rows.size + 1, dtype=np.int64) * deg).astype(np.int32)
+    Xh = np.random.default_rng(1).uniform(-1, 1, (N, F)).astype(np.float32)
+    X = torch.from_numpy(Xh).to(dev)
+    for mode, W in (("fastrand", 16), ("fastrand", 500), ("full", 0)):
+        es.es_spmm(rowptr, colidx, None, X, Y, W, mode, 0)
+        torch.cuda.synchronize()
+        Yref, den = oracle.spmm(sub_rowptr, sub_cols.reshape(-1), None, Xh, F, W, mode, 0)
+        check_Y(Y.cpu().numpy()[rows], Yref, den, f"max size {mode} W={W}")
+    del ones, X
+    # sampler export with N*W just below 2^31 (W = 510 < 511 entries per row, so FastRand samples)
+    W = 511
+    assert N * W < 2 ** 31
+    pos, cnt = es.es_spmm_sample_edges(rowptr, W - 1, "fastrand", 0)
+    torch.cuda.synchronize()
+    assert bool((cnt == W - 1).all())
+    opos, ocnt = oracle.kept(sub_rowptr, W - 1, "fastrand", 0)
+    got = pos[torch.from_numpy(rows).to(dev)].cpu().numpy().astype(np.int64) - (rows * deg)[:, None]
+    assert np.array_equal(got, opos.astype(np.int64) - sub_rowptr[:-1, None].astype(np.int64))
+    _say("max size: sampler export matches the oracle on sampled rows")
+    del pos, cnt, colidx, rowptr, Y
+    torch.cuda.empty_cache()
+
+
 def test_config5_feature_sweep_on_config3_graph(es):
     """F = 256 and F = 41 stages of the 2-layer GCN forward (layer equation of
     Section 2.1: GEMM first, then SpMM).  Dense products are formed on the host
