@@ -202,6 +202,19 @@ int32_t es_spmm_tile_slots(int32_t rows_per_wave);
 int es_spmm_set_rows_per_wave(int32_t rows_per_wave);
 
 /*
+ * Column-slicing override for es_spmm / es_spmm_norm: cap the lanes that span
+ * the feature columns at `lanes` (4, 8, 16, 32 or 64; 0 restores the built-in
+ * choice), so that one workgroup covers only 4 * lanes columns and the launch
+ * sweeps all rows once per column slice.  With lanes = 8 a gathered piece of an
+ * X row is exactly one 128-byte line, and for graphs whose column ids are
+ * clustered (community-ordered graphs) the X rows one XCD needs at a time then
+ * fit its L2.  The sampler is evaluated once per slice, so graphs without such
+ * locality only pay for it.  Same sampled edges for every value; process-wide,
+ * not thread-safe.
+ */
+int es_spmm_set_lanes_per_row(int32_t lanes);
+
+/*
  * Long-row threshold override.  A row keeping more than `entries` sampled
  * entries is not summed by one wavefront but cut into 256-entry segments that
  * several workgroups process in parallel (load balance for the skewed degree

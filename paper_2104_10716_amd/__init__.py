@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     es_spmm_max_W,
     es_spmm_norm,
     es_spmm_sample_edges,
+    es_spmm_set_lanes_per_row,
     es_spmm_set_long_row_threshold,
     es_spmm_set_rows_per_wave,
     es_spmm_status_string,

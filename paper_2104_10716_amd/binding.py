@@ -77,6 +77,8 @@ def load_library():
     lib.es_spmm_tile_slots.argtypes = [ctypes.c_int32]
     lib.es_spmm_set_rows_per_wave.restype = ctypes.c_int
     lib.es_spmm_set_rows_per_wave.argtypes = [ctypes.c_int32]
+    lib.es_spmm_set_lanes_per_row.restype = ctypes.c_int
+    lib.es_spmm_set_lanes_per_row.argtypes = [ctypes.c_int32]
     lib.es_spmm_set_long_row_threshold.restype = ctypes.c_int
     lib.es_spmm_set_long_row_threshold.argtypes = [ctypes.c_int32]
     _lib = lib
@@ -122,6 +124,12 @@ def es_spmm_set_rows_per_wave(rows_per_wave: int) -> None:
     rc = load_library().es_spmm_set_rows_per_wave(int(rows_per_wave))
     if rc != 0:
         raise EsSpmmError(rc, "es_spmm_set_rows_per_wave")
+
+
+def es_spmm_set_lanes_per_row(lanes: int) -> None:
+    rc = load_library().es_spmm_set_lanes_per_row(int(lanes))
+    if rc != 0:
+        raise EsSpmmError(rc, "es_spmm_set_lanes_per_row")
 
 
 def es_spmm_set_long_row_threshold(entries: int) -> None:

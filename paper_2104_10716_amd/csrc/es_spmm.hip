@@ -853,6 +853,7 @@ int32_t pick_long_k(const Shape& s, int logR, double entries, int F)
 
 int32_t g_force_logR = -1;   // es_spmm_set_rows_per_wave override; -1 = heuristic
 int32_t g_force_long_k = 0;  // es_spmm_set_long_row_threshold override; 0 = heuristic
+int32_t g_force_G = 0;       // es_spmm_set_lanes_per_row override; 0 = heuristic
 
 // Everything the host decides about one launch.
 struct Plan {
@@ -887,6 +888,10 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
         if (s.G < 4) s.G = 4;
         if (s.G > 64) s.G = 64;
         s.CH = F > 128 ? 4 : F > 64 ? 2 : 1;
+    }
+    if (!backward && g_force_G > 0 && s.vec == 4 && g_force_G < s.G) {
+        s.G = g_force_G;                                   // narrower column blocks, more of them
+        s.CH = 1;
     }
     p->s = s;
 
@@ -1000,6 +1005,14 @@ int es_spmm_set_rows_per_wave(int32_t rows_per_wave)
     int lg = 0;
     while ((1 << lg) < rows_per_wave) ++lg;
     g_force_logR = lg;
+    return ES_OK;
+}
+
+int es_spmm_set_lanes_per_row(int32_t lanes)
+{
+    if (lanes != 0 && lanes != 4 && lanes != 8 && lanes != 16 && lanes != 32 && lanes != 64)
+        return ES_ERR_INVALID_ARG;
+    g_force_G = lanes;
     return ES_OK;
 }
 

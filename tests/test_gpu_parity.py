@@ -24,6 +24,7 @@ def es():
     yield es
     es.es_spmm_set_rows_per_wave(0)
     es.es_spmm_set_long_row_threshold(0)
+    es.es_spmm_set_lanes_per_row(0)
 
 
 @functools.lru_cache(maxsize=2)
@@ -75,6 +76,24 @@ def test_small_graph_all_modes(es, F, ldx):
         for W in (1, 3, 8, maxdeg):
             for rpw in (0, 1, 2, 8, 64, -1):
                 check_edges(d, W, mode, 12345, rpw)
+
+
+@pytest.mark.parametrize("F", [64, 100, 256, 520])
+def test_column_slicing_override(es, F):
+    """es_spmm_set_lanes_per_row: narrower column blocks (several per row, the
+    sampler evaluated once per block) must give the same product."""
+    from gpu_util import DeviceCSR, check_against_oracle
+    rowptr, colidx, vals, X = _random_graph(900, 14.0, seed=F + 7, F=F, ldx=F + (4 - F % 4) % 4)
+    d = DeviceCSR(rowptr, colidx, vals, X, F=F)
+    for lanes in (4, 8, 16, 32, 64, 0):
+        es.es_spmm_set_lanes_per_row(lanes)
+        for thr in (0, 6):
+            es.es_spmm_set_long_row_threshold(thr)
+            for mode, W in (("full", 0), ("bucket", 5), ("fastrand", 5), ("fastrand", 25)):
+                check_against_oracle(d, W, mode, 3, norm="mean",
+                                     what=f"lanes={lanes} thr={thr} F={F} {mode} W={W}")
+    es.es_spmm_set_long_row_threshold(0)
+    es.es_spmm_set_lanes_per_row(0)
 
 
 def test_long_rows_span_several_tiles(es):

@@ -11,9 +11,11 @@ import paper_2104_10716_amd as es
 def _reset_overrides():
     es.es_spmm_set_rows_per_wave(0)
     es.es_spmm_set_long_row_threshold(0)
+    es.es_spmm_set_lanes_per_row(0)
     yield
     es.es_spmm_set_rows_per_wave(0)
     es.es_spmm_set_long_row_threshold(0)
+    es.es_spmm_set_lanes_per_row(0)
 
 
 SHAPES = [(1, 0), (7, 20), (2708, 13518), (170_000, 2_370_240), (233_000, 113_134_823),
@@ -78,6 +80,22 @@ def test_overrides_are_honoured_and_clamped():
     assert info["long_row_threshold"] == 7 and info["long_row_workgroups"] > 0
     es.es_spmm_set_long_row_threshold(0)
     assert es.es_spmm_launch_info(1000, 5000, 64, 8, "bucket")["long_row_workgroups"] == 0
+
+
+def test_column_slicing_override_only_narrows():
+    base = es.es_spmm_launch_info(1000, 9000, 128, 8, "bucket")
+    assert base["lanes_per_row"] == 32 and base["grid_y"] == 1
+    es.es_spmm_set_lanes_per_row(8)
+    sliced = es.es_spmm_launch_info(1000, 9000, 128, 8, "bucket")
+    assert sliced["lanes_per_row"] == 8 and sliced["chunks_per_lane"] == 1 and sliced["grid_y"] == 4
+    _check(sliced, 1000, 128, False)
+    wide = es.es_spmm_launch_info(1000, 9000, 16, 8, "bucket")          # already narrower than 8 lanes
+    assert wide["lanes_per_row"] == 4 and wide["grid_y"] == 1
+    bwd = es.es_spmm_launch_info(1000, 9000, 128, 8, "bucket", backward=True)
+    assert bwd["lanes_per_row"] == 64                                   # the transposed product ignores it
+    with pytest.raises(es.EsSpmmError):
+        es.es_spmm_set_lanes_per_row(12)
+    es.es_spmm_set_lanes_per_row(0)
 
 
 def test_bad_sizes_are_rejected():
