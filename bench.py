@@ -284,6 +284,7 @@ def main() -> int:
                     log(f"  cfg3 {r['mode']:8s} W={r['W']:4d}: {r['ms']:.3f} ms  {r['eff_GBps']:.0f} GB/s  "
                         f"x{r['speedup_vs_full']} vs full")
                 extra.append(presampled_ablation(dw, dev))
+                extra.append(unweighted_norm_table(dw, dev))
                 extra.append(backward_table(dw, dev, ((("fastrand", 16), ("fastrand", 64), ("bucket", 64),
                                                        ("fastrand", 256)))))
                 extra.append(gcn_feature_sweep(dw, dev, flush))
@@ -366,6 +367,29 @@ def presampled_ablation(dw, dev):
             log(f"  ablation {mode:8s} W={W:3d}: fused {t_fused:.3f} ms | materialise {t_mat:.3f} ms + "
                 f"full SpMM on pre-sampled {t_pre:.3f} ms")
             del orp, oci, ova
+    return out
+
+
+def unweighted_norm_table(dw, dev):
+    """Config 3's values are 1/d_i (mean aggregation).  The same product with no
+    value array at all: vals = NULL and the 1/n row factor applied in the kernel
+    (paper Section 6.1 moves the normalisation into the kernel) -- stage 1 then
+    reads only colidx."""
+    import torch
+    import paper_2104_10716_amd as es
+    out = {"workload": f"config-3 graph, F={dw.F}: vals = 1/d_i array vs vals = NULL + in-kernel 1/n", "rows": []}
+    Y2 = torch.empty_like(dw.Y)
+    for mode, W in (("fastrand", 16), ("fastrand", 64), ("bucket", 64), ("full", 0)):
+        t_vals = _time_fn(lambda: dw.launch(mode, W))
+        t_norm = _time_fn(lambda: es.es_spmm_norm(dw.rowptr, dw.colidx, None, dw.X, Y2, W, mode, 0,
+                                                  "inv_degree", F=dw.F))
+        dw.launch(mode, W)
+        torch.cuda.synchronize()
+        err = float((dw.Y - Y2).abs().max() / dw.Y.abs().max())
+        out["rows"].append({"mode": mode, "W": W, "with_vals_ms": round(t_vals, 4),
+                            "null_vals_inv_degree_ms": round(t_norm, 4), "max_rel_diff": err})
+        log(f"  unweighted {mode:8s} W={W:3d}: vals array {t_vals:.3f} ms | NULL + 1/n in kernel {t_norm:.3f} ms "
+            f"(max rel diff {err:.1e})")
     return out
 
 

@@ -40,7 +40,9 @@ typedef enum {
     ES_NORM_NONE = 0,     /* 1                                                     */
     ES_NORM_MEAN = 1,     /* 1 / k        mean over the kept neighbours            */
     ES_NORM_RSQRT = 2,    /* 1 / sqrt(k)  destination side of the symmetric norm   */
-    ES_NORM_RESCALE = 3   /* n / k        estimate of the full row sum             */
+    ES_NORM_RESCALE = 3,  /* n / k        estimate of the full row sum             */
+    ES_NORM_INV_DEGREE = 4 /* 1 / n       mean aggregation by the original degree:
+                                         with vals == NULL no value array is read  */
 } es_norm_t;
 
 typedef enum {

@@ -17,7 +17,7 @@ import numpy as np
 
 FULL, BUCKET, FASTRAND = 0, 1, 2
 MODES = {"full": FULL, "bucket": BUCKET, "fastrand": FASTRAND}
-NORMS = {"none": 0, "mean": 1, "rsqrt": 2, "rescale": 3}
+NORMS = {"none": 0, "mean": 1, "rsqrt": 2, "rescale": 3, "inv_degree": 4}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "es_oracle.c")

@@ -42,7 +42,9 @@
  * multiplied by a factor of its stored count n and kept count k --
  *   NONE 1;  MEAN 1/k (mean over the kept neighbours, GraphSage-mean);
  *   RSQRT 1/sqrt(k) (destination side of the symmetric GCN normalisation);
- *   RESCALE n/k (estimate of the full row sum);  rows with k = 0 stay 0.
+ *   RESCALE n/k (estimate of the full row sum);  INV_DEGREE 1/n (mean
+ *   aggregation normalised by the original degree, so an unweighted graph
+ *   needs no value array);  rows with k = 0 stay 0.
  * This part has nothing in the paper to be pinned to ("parity unpinned" against
  * the authors' kernel); it is pinned to its written definition by dense
  * brute force and by the closed forms it implies.
@@ -61,7 +63,8 @@
 #endif
 
 enum { ORACLE_FULL = 0, ORACLE_BUCKET = 1, ORACLE_FASTRAND = 2 };
-enum { ORACLE_NORM_NONE = 0, ORACLE_NORM_MEAN = 1, ORACLE_NORM_RSQRT = 2, ORACLE_NORM_RESCALE = 3 };
+enum { ORACLE_NORM_NONE = 0, ORACLE_NORM_MEAN = 1, ORACLE_NORM_RSQRT = 2, ORACLE_NORM_RESCALE = 3,
+       ORACLE_NORM_INV_DEGREE = 4 };
 
 /* One output of SplitMix64: the state is advanced by the golden-ratio
  * increment, then mixed (Steele, Lea, Flood 2014; Vigna's public-domain
@@ -124,6 +127,7 @@ double es_oracle_row_factor(int32_t norm, int64_t n, int64_t k)
     if (k == 0) return 0.0;
     if (norm == ORACLE_NORM_MEAN) return 1.0 / (double)k;
     if (norm == ORACLE_NORM_RSQRT) return 1.0 / sqrt((double)k);
+    if (norm == ORACLE_NORM_INV_DEGREE) return 1.0 / (double)n;
     return (double)n / (double)k;
 }
 
@@ -178,7 +182,7 @@ int es_oracle_spmm(const int32_t *rowptr, const int32_t *colidx, const float *va
 {
     if (!rowptr || !X || !Yref || N < 0 || F < 1 || ldx < F || nrows < 0 || bad_mode(mode))
         return -1;
-    if (norm < ORACLE_NORM_NONE || norm > ORACLE_NORM_RESCALE) return -1;
+    if (norm < ORACLE_NORM_NONE || norm > ORACLE_NORM_INV_DEGREE) return -1;
     if (mode != ORACLE_FULL && W < 1) return -1;
     if (!colidx && N > 0 && rowptr[N] > 0) return -1;
     if (rows)
@@ -231,7 +235,7 @@ int es_oracle_spmm_backward(const int32_t *rowptr, const int32_t *colidx, const 
                             int32_t mode, uint64_t seed, int32_t norm, double *dX, double *denom)
 {
     if (!rowptr || !dY || !dX || N < 0 || F < 1 || ldy < F || bad_mode(mode)) return -1;
-    if (norm < ORACLE_NORM_NONE || norm > ORACLE_NORM_RESCALE) return -1;
+    if (norm < ORACLE_NORM_NONE || norm > ORACLE_NORM_INV_DEGREE) return -1;
     if (mode != ORACLE_FULL && W < 1) return -1;
     if (!colidx && N > 0 && rowptr[N] > 0) return -1;
     for (int64_t j = 0; j < N * F; ++j) dX[j] = 0.0;

@@ -8,8 +8,9 @@ from typing import Optional
 
 ES_FULL, ES_BUCKET, ES_FASTRAND = 0, 1, 2
 MODES = {"full": ES_FULL, "bucket": ES_BUCKET, "fastrand": ES_FASTRAND}
-ES_NORM_NONE, ES_NORM_MEAN, ES_NORM_RSQRT, ES_NORM_RESCALE = 0, 1, 2, 3
-NORMS = {"none": ES_NORM_NONE, "mean": ES_NORM_MEAN, "rsqrt": ES_NORM_RSQRT, "rescale": ES_NORM_RESCALE}
+ES_NORM_NONE, ES_NORM_MEAN, ES_NORM_RSQRT, ES_NORM_RESCALE, ES_NORM_INV_DEGREE = 0, 1, 2, 3, 4
+NORMS = {"none": ES_NORM_NONE, "mean": ES_NORM_MEAN, "rsqrt": ES_NORM_RSQRT, "rescale": ES_NORM_RESCALE,
+         "inv_degree": ES_NORM_INV_DEGREE}
 
 
 

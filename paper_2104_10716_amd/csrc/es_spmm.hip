@@ -307,6 +307,7 @@ __device__ __forceinline__ float row_factor(int norm, int n, int k)
     if (k == 0) return 0.0f;
     if (norm == ES_NORM_MEAN) return 1.0f / (float)k;
     if (norm == ES_NORM_RSQRT) return 1.0f / sqrtf((float)k);
+    if (norm == ES_NORM_INV_DEGREE) return 1.0f / (float)n;
     return (float)n / (float)k;
 }
 
@@ -869,7 +870,7 @@ struct Plan {
 int check_sizes(int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W, int32_t mode,
                 int32_t norm)
 {
-    if (norm < ES_NORM_NONE || norm > ES_NORM_RESCALE) return ES_ERR_INVALID_ARG;
+    if (norm < ES_NORM_NONE || norm > ES_NORM_INV_DEGREE) return ES_ERR_INVALID_ARG;
     if (N < 0 || nnz < 0 || nnz > INT32_MAX || F < 1 || ldx < F || ldy < F) return ES_ERR_INVALID_ARG;
     if (mode != ES_FULL && mode != ES_BUCKET && mode != ES_FASTRAND) return ES_ERR_INVALID_ARG;
     if (mode != ES_FULL && W < 1) return ES_ERR_INVALID_ARG;

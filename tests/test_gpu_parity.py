@@ -187,7 +187,7 @@ def test_degenerate_inputs(es):
     assert torch.equal(Y, du.run(2, "fastrand", 5))
 
 
-@pytest.mark.parametrize("norm", ["none", "mean", "rsqrt", "rescale"])
+@pytest.mark.parametrize("norm", ["none", "mean", "rsqrt", "rescale", "inv_degree"])
 def test_in_kernel_normalisation(es, norm):
     """es_spmm_norm (Section 6.1): row factor of (n, k) applied in the kernel,
     on ordinary rows, on rows sent through the long-row path, and at full size."""

@@ -275,12 +275,13 @@ def test_row_factor_closed_forms():
     assert oracle.row_factor("mean", 10, 4) == 0.25
     assert oracle.row_factor("rsqrt", 10, 4) == 0.5
     assert oracle.row_factor("rescale", 10, 4) == 2.5
-    for norm in ("mean", "rsqrt", "rescale"):
+    assert oracle.row_factor("inv_degree", 10, 4) == 0.1
+    for norm in ("mean", "rsqrt", "rescale", "inv_degree"):
         assert oracle.row_factor(norm, 0, 0) == 0.0
     assert oracle.row_factor("none", 0, 0) == 1.0
 
 
-@pytest.mark.parametrize("norm", ["mean", "rsqrt", "rescale"])
+@pytest.mark.parametrize("norm", ["mean", "rsqrt", "rescale", "inv_degree"])
 @pytest.mark.parametrize("mode,W", [("bucket", 3), ("fastrand", 3), ("full", 0), ("fastrand", 50)])
 def test_normalised_product_vs_dense_bruteforce(norm, mode, W):
     n, F = 44, 6
@@ -293,7 +294,7 @@ def test_normalised_product_vs_dense_bruteforce(norm, mode, W):
     deg = np.diff(rowptr).astype(np.float64)
     k = cnt.astype(np.float64)
     with np.errstate(divide="ignore", invalid="ignore"):
-        f = {"mean": 1.0 / k, "rsqrt": 1.0 / np.sqrt(k), "rescale": deg / k}[norm]
+        f = {"mean": 1.0 / k, "rsqrt": 1.0 / np.sqrt(k), "rescale": deg / k, "inv_degree": 1.0 / deg}[norm]
     f = np.where(k > 0, f, 0.0)
     Y, D = oracle.spmm(rowptr, colidx, vals, X, F, W, mode, 4, norm=norm)
     Xd = X.astype(np.float64)
@@ -310,6 +311,12 @@ def test_normalisation_special_cases():
         assert np.allclose(Y, 1.0, rtol=1e-15)
         Y, _ = oracle.spmm(w.rowptr, w.colidx, None, ones, 3, W, mode, 0, norm="rescale")
         assert np.allclose(Y, np.diff(w.rowptr)[:, None], rtol=1e-15)
+    # unit values normalised by the original degree == the mean-aggregation values 1/d_i
+    w3 = make_workload(3, scale=0.005)
+    for mode, W in (("fastrand", 16), ("full", 0)):
+        Ya, Da = oracle.spmm(w3.rowptr, w3.colidx, w3.vals, w3.X, w3.F, W, mode, 0)
+        Yb, Db = oracle.spmm(w3.rowptr, w3.colidx, None, w3.X, w3.F, W, mode, 0, norm="inv_degree")
+        np.testing.assert_allclose(Yb, Ya, rtol=1e-6, atol=1e-12)      # vals are 1/d rounded to fp32
     # nothing is dropped when W covers every row: rescale is the identity
     Yn, Dn = oracle.spmm(w.rowptr, w.colidx, w.vals, w.X, w.F, w.max_degree, "fastrand", 0)
     Yr, Dr = oracle.spmm(w.rowptr, w.colidx, w.vals, w.X, w.F, w.max_degree, "fastrand", 0, norm="rescale")
