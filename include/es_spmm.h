@@ -197,8 +197,9 @@ int32_t es_spmm_tile_slots(int32_t rows_per_wave);
  * Launch-shape override for es_spmm: how many rows share one wavefront
  * (Section 4.2 assigns a thread group per row; here the group size is
  * 64 / rows_per_wave lanes).  0 restores the built-in choice; otherwise a power
- * of two in [1, 64], lowered when F needs more lanes per row.  Process-wide and
- * not thread-safe; meant for tuning sweeps and tests.  Every value yields the
+ * of two in [1, 64], lowered when F needs more lanes per row.  Process-wide
+ * (an atomic setting: a call racing with the setter sees the old or the new
+ * value); meant for tuning sweeps and tests.  Every value yields the
  * same sampled edges; Y differs only by fp32 summation order.
  */
 int es_spmm_set_rows_per_wave(int32_t rows_per_wave);
@@ -211,8 +212,8 @@ int es_spmm_set_rows_per_wave(int32_t rows_per_wave);
  * X row is exactly one 128-byte line, and for graphs whose column ids are
  * clustered (community-ordered graphs) the X rows one XCD needs at a time then
  * fit its L2.  The sampler is evaluated once per slice, so graphs without such
- * locality only pay for it.  Same sampled edges for every value; process-wide,
- * not thread-safe.
+ * locality only pay for it.  Same sampled edges for every value; process-wide
+ * atomic setting.
  */
 int es_spmm_set_lanes_per_row(int32_t lanes);
 
@@ -224,7 +225,7 @@ int es_spmm_set_lanes_per_row(int32_t lanes);
  * exceed W, so this matters for ES_FULL and for very large W).  0 restores the
  * built-in choice (derived from nnz, F and the launch shape); any positive
  * value is legal.
- * Process-wide, not thread-safe; for tuning sweeps and tests.
+ * Process-wide atomic setting; for tuning sweeps and tests.
  */
 int es_spmm_set_long_row_threshold(int32_t entries);
 

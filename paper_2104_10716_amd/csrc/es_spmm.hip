@@ -30,6 +30,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "es_spmm.h"
 
 namespace {
@@ -852,9 +854,11 @@ int32_t pick_long_k(const Shape& s, int logR, double entries, int F)
     return v < kLongMin ? kLongMin : v;
 }
 
-int32_t g_force_logR = -1;   // es_spmm_set_rows_per_wave override; -1 = heuristic
-int32_t g_force_long_k = 0;  // es_spmm_set_long_row_threshold override; 0 = heuristic
-int32_t g_force_G = 0;       // es_spmm_set_lanes_per_row override; 0 = heuristic
+// Process-wide overrides (relaxed atomics: a call racing with a setter sees
+// either the old or the new value, never a torn one).
+std::atomic<int32_t> g_force_logR{-1};   // es_spmm_set_rows_per_wave; -1 = heuristic
+std::atomic<int32_t> g_force_long_k{0};  // es_spmm_set_long_row_threshold; 0 = heuristic
+std::atomic<int32_t> g_force_G{0};       // es_spmm_set_lanes_per_row; 0 = heuristic
 
 // Everything the host decides about one launch.
 struct Plan {
@@ -890,8 +894,9 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
         if (s.G > 64) s.G = 64;
         s.CH = F > 128 ? 4 : F > 64 ? 2 : 1;
     }
-    if (!backward && g_force_G > 0 && s.vec == 4 && g_force_G < s.G) {
-        s.G = g_force_G;                                   // narrower column blocks, more of them
+    const int32_t force_G = g_force_G.load(std::memory_order_relaxed);
+    if (!backward && force_G > 0 && s.vec == 4 && force_G < s.G) {
+        s.G = force_G;                                     // narrower column blocks, more of them
         s.CH = 1;
     }
     p->s = s;
@@ -899,8 +904,9 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
     double mean = (double)nnz / (double)N;
     if (mode != ES_FULL && mean > (double)W) mean = (double)W;
     int logR = pick_logR(s, mean);
-    if (g_force_logR >= 0) {
-        logR = g_force_logR;
+    const int32_t force_logR = g_force_logR.load(std::memory_order_relaxed);
+    if (force_logR >= 0) {
+        logR = force_logR;
         while ((64 >> logR) < s.G) --logR;                 // at least one edge slot per row
     }
     p->logR = logR;
@@ -919,7 +925,8 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
     // the long-row part costs a second small launch and a scan of the row
     // pointers; below one tile per row that is more than the tail it removes
     if (mode != ES_FULL && p->long_k < kTileSlots) p->long_k = kTileSlots;
-    if (g_force_long_k > 0) p->long_k = g_force_long_k;
+    const int32_t force_long_k = g_force_long_k.load(std::memory_order_relaxed);
+    if (force_long_k > 0) p->long_k = force_long_k;
     const bool may_be_long = mode == ES_FULL || W > p->long_k;
     p->long_blocks = may_be_long ? ((N + kLongScanRows - 1) / kLongScanRows) * kLongSplit : 0;
     p->grid_x = p->per_xcd * kNumXcd + p->long_blocks;
@@ -1000,12 +1007,12 @@ int32_t es_spmm_tile_slots(int32_t rows_per_wave)
 
 int es_spmm_set_rows_per_wave(int32_t rows_per_wave)
 {
-    if (rows_per_wave == 0) { g_force_logR = -1; return ES_OK; }
+    if (rows_per_wave == 0) { g_force_logR.store(-1, std::memory_order_relaxed); return ES_OK; }
     if (rows_per_wave < 1 || rows_per_wave > 64 || (rows_per_wave & (rows_per_wave - 1)))
         return ES_ERR_INVALID_ARG;
     int lg = 0;
     while ((1 << lg) < rows_per_wave) ++lg;
-    g_force_logR = lg;
+    g_force_logR.store(lg, std::memory_order_relaxed);
     return ES_OK;
 }
 
@@ -1013,14 +1020,14 @@ int es_spmm_set_lanes_per_row(int32_t lanes)
 {
     if (lanes != 0 && lanes != 4 && lanes != 8 && lanes != 16 && lanes != 32 && lanes != 64)
         return ES_ERR_INVALID_ARG;
-    g_force_G = lanes;
+    g_force_G.store(lanes, std::memory_order_relaxed);
     return ES_OK;
 }
 
 int es_spmm_set_long_row_threshold(int32_t entries)
 {
     if (entries < 0) return ES_ERR_INVALID_ARG;
-    g_force_long_k = entries;
+    g_force_long_k.store(entries, std::memory_order_relaxed);
     return ES_OK;
 }
 
