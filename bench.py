@@ -394,10 +394,10 @@ def unweighted_norm_table(dw, dev):
 
 
 def backward_table(dw, dev, cases):
-    """es_spmm_backward (dX = sample_W(A)^T dY, fp32 atomic scatter) beside the
-    forward call of the same (mode, W).  Bytes counted: row pointers, sampled
-    (column, value) pairs, dY read once, dX zero-filled once, and one
-    read-modify-write of a dX row per kept entry."""
+    """The transposed product dX = sample_W(A)^T dY two ways, beside the forward
+    call of the same (mode, W): es_spmm_backward (fp32 atomic scatter) and the
+    pull form (es_spmm_materialize_transposed once, then a full product on the
+    transposed structure, which can be reused while (W, mode, seed) stay)."""
     import torch
     import paper_2104_10716_amd as es
     dX = torch.empty_like(dw.Y)
@@ -407,11 +407,18 @@ def backward_table(dw, dev, cases):
         t_fwd = _time_fn(lambda: dw.launch(mode, W))
         t_bwd = _time_fn(lambda: es.es_spmm_backward(dw.rowptr, dw.colidx, dw.vals, dw.X, dX, W, mode, 0,
                                                      F=dw.F))
-        B = 4 * (dw.N + 1) + 8 * kept + 2 * 4 * dw.F * dw.N + 8 * dw.F * kept
-        out["rows"].append({"mode": mode, "W": W, "forward_ms": round(t_fwd, 4), "backward_ms": round(t_bwd, 4),
-                            "backward_GBps": round(B / (t_bwd * 1e6), 1)})
-        log(f"  backward {mode:8s} W={W:3d}: {t_bwd:.3f} ms ({B / (t_bwd * 1e6):.0f} GB/s incl. atomic RMW) "
-            f"vs forward {t_fwd:.3f} ms")
+        bufs = es.es_spmm_materialize_transposed(dw.rowptr, dw.colidx, dw.vals, W, mode, 0)
+        t_build = _time_fn(lambda: es.es_spmm_materialize_transposed(dw.rowptr, dw.colidx, dw.vals, W, mode,
+                                                                     0, "none", *bufs))
+        ptr, _, idx, val = bufs
+        idx, val = idx[:kept], val[:kept]
+        t_pull = _time_fn(lambda: es.es_spmm(ptr, idx, val, dw.X, dX, 0, "full", F=dw.F))
+        out["rows"].append({"mode": mode, "W": W, "forward_ms": round(t_fwd, 4),
+                            "backward_atomic_ms": round(t_bwd, 4), "transpose_build_ms": round(t_build, 4),
+                            "backward_pull_ms": round(t_pull, 4)})
+        log(f"  backward {mode:8s} W={W:3d}: atomic scatter {t_bwd:.3f} ms | transposed build {t_build:.3f} ms "
+            f"+ pull {t_pull:.3f} ms | forward {t_fwd:.3f} ms")
+        del bufs, ptr, idx, val
     return out
 
 

@@ -156,6 +156,27 @@ int es_spmm_materialize(const int32_t* rowptr, const int32_t* colidx, const floa
                         void* stream);
 
 /*
+ * es_spmm_materialize_transposed -- the TRANSPOSE of the sampled graph as a CSR
+ * matrix of its own (the sampled graph in CSC form).  Row c of the output lists,
+ * for every kept entry of es_spmm_norm(..., W, mode, seed, norm) whose column is
+ * c, the row r it came from and the value factor_r * vals[p].  With it the
+ * backward pass is a gather instead of an atomic scatter:
+ *     es_spmm(out_ptr, out_idx, out_vals, dY, dX, ..., ES_FULL)
+ * computes the same dX as es_spmm_backward, and the structure can be reused for
+ * every product that shares (W, mode, seed, norm).
+ *   out_ptr  [N+1] int32, written: start of each output row (out_ptr[N] = kept total)
+ *   out_end  [N]   int32, written: end of each output row (= out_ptr[c+1]); the
+ *            build advances it entry by entry, so it is an output, not scratch
+ *   out_idx, out_vals: written; capacity at least min(nnz, N*W) entries
+ * The order of the entries inside an output row is unspecified (they are placed
+ * through an atomic cursor) and may differ from launch to launch.
+ */
+int es_spmm_materialize_transposed(const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                                   int64_t N, int64_t nnz, int32_t W, int32_t mode, uint64_t seed,
+                                   int32_t norm, int32_t* out_ptr, int32_t* out_end,
+                                   int32_t* out_idx, float* out_vals, void* stream);
+
+/*
  * es_spmm_launch_info -- the launch shape es_spmm_norm (backward == 0) or
  * es_spmm_backward (backward != 0) would pick for these sizes, without
  * launching anything and without a GPU.  `aligned16`: both matrices are

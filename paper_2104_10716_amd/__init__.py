@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     es_spmm_backward,
     es_spmm_launch_info,
     es_spmm_materialize,
+    es_spmm_materialize_transposed,
     es_spmm_max_W,
     es_spmm_norm,
     es_spmm_sample_edges,

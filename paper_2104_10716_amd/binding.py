@@ -66,6 +66,10 @@ def load_library():
     lib.es_spmm_materialize.restype = ctypes.c_int
     lib.es_spmm_materialize.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
                                         ctypes.c_int32, ctypes.c_uint64, vp, vp, vp, vp]
+    lib.es_spmm_materialize_transposed.restype = ctypes.c_int
+    lib.es_spmm_materialize_transposed.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int64,
+                                                   ctypes.c_int32, ctypes.c_int32, ctypes.c_uint64,
+                                                   ctypes.c_int32, vp, vp, vp, vp, vp]
     lib.es_spmm_launch_info.restype = ctypes.c_int
     lib.es_spmm_launch_info.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                         ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
@@ -264,3 +268,37 @@ def es_spmm_launch_info(N: int, nnz: int, F: int, W: int, mode, ldx: Optional[in
     if rc != 0:
         raise EsSpmmError(rc, "es_spmm_launch_info")
     return {name: int(getattr(info, name)) for name, _ in es_launch_info_t._fields_}
+
+
+def es_spmm_materialize_transposed(rowptr, colidx, vals, W: int, mode, seed: int = 0, norm="none",
+                                   out_ptr=None, out_end=None, out_idx=None, out_vals=None, stream=None):
+    """Transposed sampled graph as CSR tensors (out_ptr [N+1], out_end [N], out_idx, out_vals);
+    index / value arrays are allocated at the capacity bound min(nnz, N*W)."""
+    import torch
+    lib = load_library()
+    N = rowptr.numel() - 1
+    nnz = colidx.numel()
+    m = _mode(mode)
+    cap = nnz if m == ES_FULL else min(nnz, N * int(W))
+    dev = rowptr.device
+    if out_ptr is None:
+        out_ptr = torch.empty((N + 1,), dtype=torch.int32, device=dev)
+    if out_end is None:
+        out_end = torch.empty((N,), dtype=torch.int32, device=dev)
+    if out_idx is None:
+        out_idx = torch.empty((cap,), dtype=torch.int32, device=dev)
+    if out_vals is None:
+        out_vals = torch.empty((cap,), dtype=torch.float32, device=dev)
+    if (out_ptr.numel() != N + 1 or out_end.numel() != N or out_idx.numel() < cap
+            or out_vals.numel() < cap):
+        raise ValueError("output tensors are too small")
+    nm = NORMS[norm] if isinstance(norm, str) else int(norm)
+    rc = lib.es_spmm_materialize_transposed(
+        _dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(colidx, torch.int32, "colidx"),
+        _dev_ptr(vals, torch.float32, "vals"), N, nnz, int(W), m, int(seed) & 0xFFFFFFFFFFFFFFFF, nm,
+        _dev_ptr(out_ptr, torch.int32, "out_ptr"), _dev_ptr(out_end, torch.int32, "out_end"),
+        _dev_ptr(out_idx, torch.int32, "out_idx"), _dev_ptr(out_vals, torch.float32, "out_vals"),
+        _stream_ptr(stream))
+    if rc != 0:
+        raise EsSpmmError(rc, "es_spmm_materialize_transposed")
+    return out_ptr, out_end, out_idx, out_vals

@@ -649,10 +649,12 @@ es_sample_edges_kernel(const int32_t* __restrict__ rowptr, int64_t N, int32_t W,
 constexpr int kScanRows = 1024;                       // rows per scan workgroup
 constexpr int kScanPerThread = kScanRows / kBlockThreads;
 
-// Step 1: out[r+1] = inclusive prefix of k inside the row's 1024-row block.
+// Step 1: out[r+1] = inclusive prefix, inside the row's 1024-row block, of the
+// kept counts k_r (rowptr given) or of the counts already stored in out[r+1]
+// (rowptr == nullptr; each thread reads its own entries before it writes them).
 __global__ void __launch_bounds__(kBlockThreads)
 es_kept_scan_local_kernel(const int32_t* __restrict__ rowptr, int64_t N, int32_t W, int32_t mode,
-                          int32_t* __restrict__ out)
+                          int32_t* out)
 {
     __shared__ int wave_total[kWavesPerBlock];
     const int tid = threadIdx.x;
@@ -664,7 +666,8 @@ es_kept_scan_local_kernel(const int32_t* __restrict__ rowptr, int64_t N, int32_t
 #pragma unroll
     for (int i = 0; i < kScanPerThread; ++i) {
         const int64_t r = r0 + i;
-        k[i] = (r < N) ? kept_count(mode, rowptr[r + 1] - rowptr[r], W) : 0;
+        k[i] = 0;
+        if (r < N) k[i] = rowptr ? kept_count(mode, rowptr[r + 1] - rowptr[r], W) : out[r + 1];
         mine += k[i];
     }
     int incl = mine;
@@ -758,6 +761,67 @@ es_materialize_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restr
             const int64_t p = (int64_t)base + entry;
             out_colidx[obase + t0 + slot] = colidx[p];
             out_vals[obase + t0 + slot] = vals ? vals[p] : 1.0f;
+        });
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Transposed sampled graph (the sampled graph in CSC form): count the kept
+// entries per column, scan, then drop every entry into its column's segment
+// through a per-column cursor.  Entries of one column arrive in no fixed order.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlockThreads) es_fill_int_kernel(int32_t* out, int64_t n, int32_t v)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kBlockThreads + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * kBlockThreads)
+        out[i] = v;
+}
+
+__global__ void __launch_bounds__(kBlockThreads)
+es_copy_int_kernel(const int32_t* __restrict__ in, int32_t* __restrict__ out, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kBlockThreads + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * kBlockThreads)
+        out[i] = in[i];
+}
+
+// FILL == false: out_ptr[c + 1] += 1 per kept entry with column c.
+// FILL == true : the entry goes to position out_end[c]++ of out_idx / out_vals
+//                (value times the row factor).
+template <bool FILL>
+__global__ void __launch_bounds__(kBlockThreads)
+es_transpose_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+                    const float* __restrict__ vals, int64_t N, int32_t W, int32_t mode, uint64_t seed,
+                    int32_t norm, int32_t logR, int32_t* out_ptr, int32_t* out_end,
+                    int32_t* __restrict__ out_idx, float* __restrict__ out_vals)
+{
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = threadIdx.x >> 6;
+    const int team = kWaveSize >> logR;
+    const int rs = lane >> (6 - logR);
+    const int t = lane & (team - 1);
+    const int T = kTileSlots >> logR;
+    const int64_t r = ((((int64_t)blockIdx.x * kWavesPerBlock) + wave) << logR) + rs;
+    if (r >= N) return;
+    const int32_t base = rowptr[r];
+    const int32_t n = rowptr[r + 1] - base;
+    const int k = kept_count(mode, n, W);
+    const float f = row_factor(norm, n, k);
+
+    RowSampler sampler;
+    sampler.init(mode, seed, r, (uint32_t)n, (uint32_t)W, (uint32_t)t, (uint32_t)team);
+    for (int t0 = 0; t0 < k; t0 += T) {
+        const int count = min(k - t0, T);
+        sample_tile(sampler, t, team, count, [&](int, uint32_t entry) {
+            const int64_t p = (int64_t)base + entry;
+            const int32_t c = colidx[p];
+            if (!FILL) {
+                atomicAdd(out_ptr + c + 1, 1);
+            } else {
+                const int32_t pos = atomicAdd(out_end + c, 1);
+                out_idx[pos] = (int32_t)r;
+                out_vals[pos] = f * (vals ? vals[p] : 1.0f);
+            }
         });
     }
 }
@@ -859,6 +923,19 @@ int32_t pick_long_k(const Shape& s, int logR, double entries, int F)
 std::atomic<int32_t> g_force_logR{-1};   // es_spmm_set_rows_per_wave; -1 = heuristic
 std::atomic<int32_t> g_force_long_k{0};  // es_spmm_set_long_row_threshold; 0 = heuristic
 std::atomic<int32_t> g_force_G{0};       // es_spmm_set_lanes_per_row; 0 = heuristic
+
+// Rows per wave for the kernels that only walk the sampler (materialise,
+// transpose): about one lane per kept entry of a typical row; a whole wave per
+// row when rows may be much longer than typical (full mode, W above a wave).
+int walk_logR(int64_t N, int64_t nnz, int32_t Wk)
+{
+    if (Wk > kWaveSize) return 0;
+    double mean = (double)nnz / (double)N;
+    if (mean > (double)Wk) mean = (double)Wk;
+    int logR = 6;
+    while (logR > 0 && (double)(kWaveSize >> logR) < mean) --logR;
+    return logR;
+}
 
 // Everything the host decides about one launch.
 struct Plan {
@@ -1104,17 +1181,65 @@ int es_spmm_materialize(const int32_t* rowptr, const int32_t* colidx, const floa
                            st, N, out_rowptr);
         if (hipGetLastError() != hipSuccess) return ES_ERR_LAUNCH;
     }
-    // lanes per row: about one per kept entry of a typical row
-    double mean = (double)nnz / (double)N;
-    if (mean > (double)Wk) mean = (double)Wk;
-    int logR = 6;
-    while (logR > 0 && (double)(kWaveSize >> logR) < mean) --logR;
+    const int logR = walk_logR(N, nnz, Wk);
     const int64_t rows_per_block = (int64_t)kWavesPerBlock << logR;
     const int64_t nblocks = (N + rows_per_block - 1) / rows_per_block;
     if (nblocks > INT32_MAX) return ES_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(es_materialize_kernel, dim3((uint32_t)nblocks), dim3(kBlockThreads), 0, st,
                        rowptr, colidx, vals, N, Wk, mode, seed, logR, out_rowptr, out_colidx, out_vals);
     return hipGetLastError() == hipSuccess ? ES_OK : ES_ERR_LAUNCH;
+}
+
+int es_spmm_materialize_transposed(const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                                   int64_t N, int64_t nnz, int32_t W, int32_t mode, uint64_t seed,
+                                   int32_t norm, int32_t* out_ptr, int32_t* out_end, int32_t* out_idx,
+                                   float* out_vals, void* stream)
+{
+    if (N < 0 || nnz < 0 || nnz > INT32_MAX) return ES_ERR_INVALID_ARG;
+    if (mode != ES_FULL && mode != ES_BUCKET && mode != ES_FASTRAND) return ES_ERR_INVALID_ARG;
+    if (mode != ES_FULL && W < 1) return ES_ERR_INVALID_ARG;
+    if (norm < ES_NORM_NONE || norm > ES_NORM_INV_DEGREE) return ES_ERR_INVALID_ARG;
+    if (!out_ptr) return ES_ERR_INVALID_ARG;
+    if (N > 0 && (!rowptr || !out_end || !out_idx || !out_vals)) return ES_ERR_INVALID_ARG;
+    if (nnz > 0 && !colidx) return ES_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int32_t Wk = (mode == ES_FULL) ? INT32_MAX : W;
+    const int64_t nscan = N == 0 ? 1 : (N + kScanRows - 1) / kScanRows;
+    if (nscan > INT32_MAX) return ES_ERR_UNSUPPORTED;
+#define ES_CHECK_LAUNCH() if (hipGetLastError() != hipSuccess) return ES_ERR_LAUNCH
+    int64_t fb = (N + 1 + kBlockThreads - 1) / kBlockThreads;
+    if (fb > 65536) fb = 65536;
+    hipLaunchKernelGGL(es_fill_int_kernel, dim3((uint32_t)fb), dim3(kBlockThreads), 0, st, out_ptr, N + 1, 0);
+    ES_CHECK_LAUNCH();
+    if (N == 0) return ES_OK;
+
+    const int logR = walk_logR(N, nnz, Wk);
+    const int64_t rows_per_block = (int64_t)kWavesPerBlock << logR;
+    const int64_t nblocks = (N + rows_per_block - 1) / rows_per_block;
+    if (nblocks > INT32_MAX) return ES_ERR_UNSUPPORTED;
+
+    hipLaunchKernelGGL(es_transpose_kernel<false>, dim3((uint32_t)nblocks), dim3(kBlockThreads), 0, st,
+                       rowptr, colidx, vals, N, Wk, mode, seed, norm, logR, out_ptr, out_end, out_idx,
+                       out_vals);
+    ES_CHECK_LAUNCH();
+    hipLaunchKernelGGL(es_kept_scan_local_kernel, dim3((uint32_t)nscan), dim3(kBlockThreads), 0, st,
+                       static_cast<const int32_t*>(nullptr), N, Wk, mode, out_ptr);
+    ES_CHECK_LAUNCH();
+    if (nscan > 1) {
+        hipLaunchKernelGGL(es_kept_scan_blocks_kernel, dim3(1), dim3(kBlockThreads), 0, st, N, out_ptr);
+        ES_CHECK_LAUNCH();
+        hipLaunchKernelGGL(es_kept_scan_add_kernel, dim3((uint32_t)(nscan - 1)), dim3(kBlockThreads), 0,
+                           st, N, out_ptr);
+        ES_CHECK_LAUNCH();
+    }
+    hipLaunchKernelGGL(es_copy_int_kernel, dim3((uint32_t)fb), dim3(kBlockThreads), 0, st, out_ptr, out_end, N);
+    ES_CHECK_LAUNCH();
+    hipLaunchKernelGGL(es_transpose_kernel<true>, dim3((uint32_t)nblocks), dim3(kBlockThreads), 0, st,
+                       rowptr, colidx, vals, N, Wk, mode, seed, norm, logR, out_ptr, out_end, out_idx,
+                       out_vals);
+    ES_CHECK_LAUNCH();
+#undef ES_CHECK_LAUNCH
+    return ES_OK;
 }
 
 int es_spmm_sample_edges(const int32_t* rowptr, int64_t N, int32_t W, int32_t mode, uint64_t seed,

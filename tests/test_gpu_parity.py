@@ -258,6 +258,54 @@ def test_backward_full_size(es):
         del d, Xd, Y, dX
 
 
+def _oracle_transposed(rowptr, colidx, vals, W, mode, seed):
+    """(column, row, value) of every kept entry, sorted by (column, row)."""
+    import oracle
+    pos, cnt = oracle.kept(rowptr, W, mode, seed)
+    rows = np.repeat(np.arange(rowptr.shape[0] - 1), cnt)
+    keep = pos[pos >= 0] if pos.shape[1] else np.zeros(0, dtype=np.int32)
+    c = colidx[keep].astype(np.int64)
+    v = np.ones(keep.size, dtype=np.float32) if vals is None else vals[keep]
+    order = np.lexsort((rows, c))
+    return c[order], rows[order], v[order]
+
+
+@pytest.mark.parametrize("n,avg", [(1, 2.0), (700, 9.0), (40_000, 12.0)])
+def test_transposed_sampled_graph(es, n, avg):
+    """es_spmm_materialize_transposed: the structure holds exactly the oracle's
+    kept entries, grouped by column (order inside a group is free), and the
+    full product on it equals the oracle's transposed product."""
+    import torch
+    import oracle
+    from gpu_util import DeviceCSR, check_Y
+    rowptr, colidx, vals, dY = _random_graph(n, avg, seed=n + 3, F=20, empty_frac=0.2 if n > 1 else 0.0)
+    d = DeviceCSR(rowptr, colidx, vals, dY)
+    maxdeg = max(1, int(np.diff(rowptr).max()))
+    for mode, W in (("bucket", 3), ("fastrand", 3), ("fastrand", maxdeg + 2), ("full", 0)):
+        for seed in (0, 5):
+            ptr, end, idx, val = es.es_spmm_materialize_transposed(d.rowptr, d.colidx, d.vals, W, mode, seed)
+            torch.cuda.synchronize()
+            ptr_h, end_h = ptr.cpu().numpy(), end.cpu().numpy()
+            ec, er, ev = _oracle_transposed(rowptr, colidx, vals, W, mode, seed)
+            total = ec.size
+            assert ptr_h[0] == 0 and ptr_h[-1] == total
+            assert np.array_equal(np.diff(ptr_h), np.bincount(ec, minlength=n)), (mode, W, seed)
+            assert np.array_equal(end_h, ptr_h[1:])
+            gc = np.repeat(np.arange(n), np.diff(ptr_h))
+            gr = idx.cpu().numpy()[:total].astype(np.int64)
+            gv = val.cpu().numpy()[:total]
+            order = np.lexsort((gr, gc))
+            assert np.array_equal(gr[order], er) and np.array_equal(gv[order], ev), (mode, W, seed)
+    for norm in ("none", "mean", "inv_degree"):
+        ptr, end, idx, val = es.es_spmm_materialize_transposed(d.rowptr, d.colidx, d.vals, 4, "fastrand", 9, norm)
+        total = int(ptr[-1].item())
+        dX = torch.full((d.N, d.F), float("nan"), dtype=torch.float32, device="cuda:0")
+        es.es_spmm(ptr, idx[:total], val[:total], d.X, dX, 0, "full")
+        torch.cuda.synchronize()
+        ref, den = oracle.spmm_backward(rowptr, colidx, vals, dY, d.F, 4, "fastrand", 9, norm=norm)
+        check_Y(dX.cpu().numpy(), ref, den, f"pull backward n={n} norm={norm}")
+
+
 def test_hip_graph_capture_and_replay(es):
     """es_spmm only enqueues kernels, so a caller can capture it in a HIP graph.
     Replays (with eager work and synchronisations in between) must reproduce the
