@@ -1,0 +1,41 @@
+// es_common.h -- constants and the kernel argument block shared by every kernel of the library.
+#ifndef ES_SPMM_COMMON_H
+#define ES_SPMM_COMMON_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "es_spmm.h"
+
+namespace {
+
+constexpr int kWaveSize = 64;
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlockThreads = kWaveSize * kWavesPerBlock;
+constexpr int kTileSlots = 512;                       // (col, val) slots per wave
+constexpr int kWaveTileStride = kTileSlots + 64;      // + one pad slot per row slot
+constexpr int kNumXcd = 8;
+constexpr int kLongScanRows = 1024;                   // rows one long-row workgroup scans
+constexpr int kLongSplit = 16;                        // workgroups sharing those rows
+constexpr int kLongSeg = 256;                         // slots per long-row segment (<= kTileSlots)
+constexpr int kLongMin = 64;                          // smallest long-row threshold the host picks
+static_assert(kLongSplit % kNumXcd == 0, "long-row workgroups must not shift the XCD phase");
+
+struct Args {
+    const int32_t* rowptr;
+    const int32_t* colidx;
+    const float* vals;
+    const float* X;
+    float* Y;
+    int64_t N;
+    uint64_t seed;
+    int32_t F, ldx, ldy, W, mode, logR;
+    int32_t long_k;            // rows keeping more entries go to the long-row part  
+    int32_t norm;              // es_norm_t: row factor applied before the store
+    uint32_t nblocks;          // workgroups that carry rows
+    uint32_t blocks_per_xcd;   // ceil(nblocks / 8)
+    uint32_t long_blocks;      // leading workgroups that run the long-row part
+};
+
+}  // namespace
+
+#endif  // ES_SPMM_COMMON_H

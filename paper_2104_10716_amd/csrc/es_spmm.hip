@@ -34,797 +34,13 @@
 
 #include "es_spmm.h"
 
+#include "es_common.h"
+#include "es_sampler.h"
+#include "es_tile.h"
+#include "es_fused_kernel.h"
+#include "es_aux_kernels.h"
+
 namespace {
-
-constexpr int kWaveSize = 64;
-constexpr int kWavesPerBlock = 4;
-constexpr int kBlockThreads = kWaveSize * kWavesPerBlock;
-constexpr int kTileSlots = 512;                       // (col, val) slots per wave
-constexpr int kWaveTileStride = kTileSlots + 64;      // + one pad slot per row slot
-constexpr int kNumXcd = 8;
-constexpr int kLongScanRows = 1024;                   // rows one long-row workgroup scans
-constexpr int kLongSplit = 16;                        // workgroups sharing those rows
-constexpr int kLongSeg = 256;                         // slots per long-row segment (<= kTileSlots)
-constexpr int kLongMin = 64;                          // smallest long-row threshold the host picks
-static_assert(kLongSplit % kNumXcd == 0, "long-row workgroups must not shift the XCD phase");
-
-struct Args {
-    const int32_t* rowptr;
-    const int32_t* colidx;
-    const float* vals;
-    const float* X;
-    float* Y;
-    int64_t N;
-    uint64_t seed;
-    int32_t F, ldx, ldy, W, mode, logR;
-    int32_t long_k;            // rows keeping more entries go to the long-row part  
-    int32_t norm;              // es_norm_t: row factor applied before the store
-    uint32_t nblocks;          // workgroups that carry rows
-    uint32_t blocks_per_xcd;   // ceil(nblocks / 8)
-    uint32_t long_blocks;      // leading workgroups that run the long-row part
-};
-
-// ---------------------------------------------------------------------------
-// Sampler (Section 4.4).  One instance per lane walks the slots
-// first, first + stride, first + 2*stride, ... of one row and returns the entry
-// number inside the row for each.  Bucket / full / short rows: the slot number
-// itself.  FastRand on a long row: (off + slot * P) mod n, kept incrementally
-// (one add and one conditional subtract per slot instead of a modulo).
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ uint64_t splitmix64_output(uint64_t seed, uint64_t count)
-{
-    // `count`-th output (1-based) of SplitMix64 seeded with `seed`
-    uint64_t z = seed + count * 0x9E3779B97F4A7C15ull;
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
-
-struct RowSampler {
-    uint32_t idx;    // entry number the next call returns
-    uint32_t step;   // increment per call, already reduced mod n
-    uint32_t wrap;   // n for FastRand, 0xFFFFFFFF when no wrap can happen
-
-    // requires stride <= 64
-    __device__ __forceinline__ void init(int mode, uint64_t seed, int64_t row, uint32_t n,
-                                         uint32_t W, uint32_t first, uint32_t stride)
-    {
-        if (mode != ES_FASTRAND || n <= W) {
-            idx = first;
-            step = stride;
-            wrap = 0xFFFFFFFFu;
-            return;
-        }
-        const uint32_t P = (n % 577u) ? 577u : (n % 587u) ? 587u : (n % 593u) ? 593u : 599u;
-        uint32_t off = 0;
-        if (seed != 0)
-            off = (uint32_t)(splitmix64_output(seed, (uint64_t)row + 1u) >> 32) % n;
-        if (first < 65536u)
-            idx = (off + (first * P) % n) % n;               // both terms < n < 2^31
-        else
-            idx = (uint32_t)(((uint64_t)off + (uint64_t)first * P) % n);
-        step = (stride * P) % n;
-        wrap = n;
-    }
-
-    __device__ __forceinline__ uint32_t next()
-    {
-        const uint32_t cur = idx;
-        uint32_t nx = idx + step;          // < 2n < 2^32
-        if (nx >= wrap) nx -= wrap;
-        idx = nx;
-        return cur;
-    }
-};
-
-// Stage 1 for one tile: lane t of a team of `team` lanes handles slots
-// t, t + team, ... < count and hands (slot, entry number) to the sink.
-template <class Sink>
-__device__ __forceinline__ void sample_tile(RowSampler& s, int t, int team, int count, Sink&& sink)
-{
-    for (int i = t; i < count; i += team) sink(i, s.next());
-}
-
-// Orders a wave's LDS writes before its later LDS reads (and the reverse for
-// tile reuse).  The hardware executes one wave's LDS operations in order; this
-// only stops the compiler from moving them across.
-__device__ __forceinline__ void wave_lds_fence()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// ---------------------------------------------------------------------------
-// VEC-wide pieces of a row of X / Y
-// ---------------------------------------------------------------------------
-// ALIGNED = false: rows of X / Y are only 4-byte aligned (F or a row stride is
-// not a multiple of 4).  Loads stay 128-bit (the HSA ABI runs the memory
-// pipeline in unaligned-access mode); a row's last, partial chunk is read as
-// the row's final four floats and only its components >= `first` are kept.
-typedef float float4_a4 __attribute__((ext_vector_type(4), aligned(4)));
-
-template <int VEC, bool ALIGNED> struct Pack;
-template <bool ALIGNED> struct Pack<4, ALIGNED> {
-    float4 v;
-    __device__ __forceinline__ void zero() { v = make_float4(0.f, 0.f, 0.f, 0.f); }
-    __device__ __forceinline__ void load(const float* p)
-    {
-        if (ALIGNED) {
-            v = *reinterpret_cast<const float4*>(p);
-        } else {
-            const float4_a4 t = *reinterpret_cast<const float4_a4*>(p);
-            v = make_float4(t.x, t.y, t.z, t.w);
-        }
-    }
-    __device__ __forceinline__ void store(float* p, int first) const
-    {
-        if (ALIGNED) {
-            *reinterpret_cast<float4*>(p) = v;
-        } else {
-            if (first <= 0) p[0] = v.x;
-            if (first <= 1) p[1] = v.y;
-            if (first <= 2) p[2] = v.z;
-            p[3] = v.w;
-        }
-    }
-    __device__ __forceinline__ void atomic_add(float* p, int first) const
-    {
-        if (first <= 0) unsafeAtomicAdd(p, v.x);
-        if (first <= 1) unsafeAtomicAdd(p + 1, v.y);
-        if (first <= 2) unsafeAtomicAdd(p + 2, v.z);
-        unsafeAtomicAdd(p + 3, v.w);
-    }
-    __device__ __forceinline__ void fma(float a, const Pack& x)
-    {
-        v.x = fmaf(a, x.v.x, v.x); v.y = fmaf(a, x.v.y, v.y);
-        v.z = fmaf(a, x.v.z, v.z); v.w = fmaf(a, x.v.w, v.w);
-    }
-    __device__ __forceinline__ void scale(float f) { v.x *= f; v.y *= f; v.z *= f; v.w *= f; }
-    __device__ __forceinline__ void add_xor(int mask)
-    {
-        v.x += __shfl_xor(v.x, mask, kWaveSize); v.y += __shfl_xor(v.y, mask, kWaveSize);
-        v.z += __shfl_xor(v.z, mask, kWaveSize); v.w += __shfl_xor(v.w, mask, kWaveSize);
-    }
-};
-template <bool ALIGNED> struct Pack<1, ALIGNED> {
-    float v;
-    __device__ __forceinline__ void zero() { v = 0.f; }
-    __device__ __forceinline__ void load(const float* p) { v = *p; }
-    __device__ __forceinline__ void store(float* p, int) const { *p = v; }
-    __device__ __forceinline__ void atomic_add(float* p, int) const { unsafeAtomicAdd(p, v); }
-    __device__ __forceinline__ void fma(float a, const Pack& x) { v = fmaf(a, x.v, v); }
-    __device__ __forceinline__ void scale(float f) { v *= f; }
-    __device__ __forceinline__ void add_xor(int mask) { v += __shfl_xor(v, mask, kWaveSize); }
-};
-
-constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v >> 1); }
-
-// Feature columns one lane covers: CH chunks of VEC floats, chunk ch at column
-// colblk + (ch*G + l)*VEC.  Lanes past F re-read column 0 and never store.  In
-// the unaligned variant a chunk that straddles F is moved back to end at F and
-// `first` marks its first component that belongs to this lane.
-template <int G, int CH, int VEC, bool ALIGNED>
-struct LaneCols {
-    int off[CH];
-    int first[CH];
-    bool ok[CH];
-    __device__ __forceinline__ void init(int colblk, int l, int F)
-    {
-#pragma unroll
-        for (int ch = 0; ch < CH; ++ch) {
-            const int c = colblk + (ch * G + l) * VEC;
-            ok[ch] = c < F;
-            off[ch] = ok[ch] ? c : 0;
-            first[ch] = 0;
-            if (!ALIGNED && VEC > 1 && ok[ch] && c + VEC > F) {
-                off[ch] = F - VEC;
-                first[ch] = c - off[ch];
-            }
-        }
-    }
-};
-
-// Stage 1 of Algorithm 1 for one tile: copy the sampled (column, value) pairs
-// of slots [0, count) into the LDS tile.
-__device__ __forceinline__ void stage_tile(RowSampler& sampler, int t, int team, int count,
-                                           int32_t base, const int32_t* __restrict__ colidx,
-                                           const float* __restrict__ vals, uint2* tile)
-{
-    sample_tile(sampler, t, team, count, [&](int slot, uint32_t entry) {
-        const int64_t p = (int64_t)base + entry;
-        const int32_t c = colidx[p];
-        const float v = vals ? vals[p] : 1.0f;
-        tile[slot] = make_uint2((uint32_t)c, __float_as_uint(v));
-    });
-}
-
-// Stage 2 of Algorithm 1 for one tile: this lane's edge slot e (of E) walks
-// tile entries e, e+E, ... < count, U at a time: U LDS broadcasts, then U*CH
-// independent loads of X, then the FMAs.
-template <int G, int CH, int VEC, bool ALIGNED>
-__device__ __forceinline__ void consume_tile(const uint2* tile, int count, int e, int E,
-                                             const float* __restrict__ X, int64_t ldx,
-                                             const LaneCols<G, CH, VEC, ALIGNED>& cols,
-                                             Pack<VEC, ALIGNED> (&acc)[CH])
-{
-    constexpr int U = 8 / CH;
-    using P = Pack<VEC, ALIGNED>;
-    int j = e;
-    for (; j + (U - 1) * E < count; j += U * E) {            // full batches
-        uint2 ed[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) ed[u] = tile[j + u * E];
-        P x[U][CH];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float* xr = X + (int64_t)ed[u].x * ldx;
-#pragma unroll
-            for (int ch = 0; ch < CH; ++ch) x[u][ch].load(xr + cols.off[ch]);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float v = __uint_as_float(ed[u].y);
-#pragma unroll
-            for (int ch = 0; ch < CH; ++ch) acc[ch].fma(v, x[u][ch]);
-        }
-    }
-    if (j < count) {                                         // last partial batch
-        uint2 ed[U];
-        bool ok[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int jj = j + u * E;
-            ok[u] = jj < count;
-            ed[u] = tile[ok[u] ? jj : j];                    // absent slots re-read a present one
-        }
-        P x[U][CH];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float* xr = X + (int64_t)ed[u].x * ldx;
-#pragma unroll
-            for (int ch = 0; ch < CH; ++ch) x[u][ch].load(xr + cols.off[ch]);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float v = __uint_as_float(ed[u].y);
-            if (ok[u]) {
-#pragma unroll
-                for (int ch = 0; ch < CH; ++ch) acc[ch].fma(v, x[u][ch]);
-            }
-        }
-    }
-}
-
-__device__ __forceinline__ int kept_count(int mode, int n, int W)
-{
-    return (mode == ES_FULL) ? n : min(n, W);
-}
-
-// Row factor of the in-kernel normalisation (Section 6.1): a function of the
-// row's stored count n and kept count k; rows that keep nothing stay zero.
-__device__ __forceinline__ float row_factor(int norm, int n, int k)
-{
-    if (norm == ES_NORM_NONE) return 1.0f;
-    if (k == 0) return 0.0f;
-    if (norm == ES_NORM_MEAN) return 1.0f / (float)k;
-    if (norm == ES_NORM_RSQRT) return 1.0f / sqrtf((float)k);
-    if (norm == ES_NORM_INV_DEGREE) return 1.0f / (float)n;
-    return (float)n / (float)k;
-}
-
-// Transposed stage 2 (backward pass): every staged entry (c, v) of the tile adds
-// v * dy to row c of the output with fp32 atomics; edge slot e of E walks
-// entries e, e+E, ...  Atomics return nothing, so they pipeline by themselves.
-template <int G, int CH, int VEC, bool ALIGNED>
-__device__ __forceinline__ void scatter_tile(const uint2* tile, int count, int e, int E, float* out,
-                                             int64_t ldo, const LaneCols<G, CH, VEC, ALIGNED>& cols,
-                                             const Pack<VEC, ALIGNED> (&dy)[CH])
-{
-    for (int j = e; j < count; j += E) {
-        const uint2 ed = tile[j];
-        const float v = __uint_as_float(ed.y);
-        float* dst = out + (int64_t)ed.x * ldo;
-#pragma unroll
-        for (int ch = 0; ch < CH; ++ch) {
-            if (cols.ok[ch]) {
-                Pack<VEC, ALIGNED> t = dy[ch];
-                t.scale(v);
-                t.atomic_add(dst + cols.off[ch], cols.first[ch]);
-            }
-        }
-    }
-}
-
-// This lane's chunks of row r of the upstream gradient, times the row factor.
-template <int G, int CH, int VEC, bool ALIGNED>
-__device__ __forceinline__ void load_row_chunks(const Args& a, int64_t r, int n, int k,
-                                                const LaneCols<G, CH, VEC, ALIGNED>& cols,
-                                                Pack<VEC, ALIGNED> (&dy)[CH])
-{
-    const float f = row_factor(a.norm, n, k);
-    const float* src = a.X + r * (int64_t)a.ldx;
-#pragma unroll
-    for (int ch = 0; ch < CH; ++ch) {
-        dy[ch].load(src + cols.off[ch]);
-        dy[ch].scale(f);
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Row part of the fused kernel (Algorithm 1) for workgroup `vb` of the row
-// grid.  G lanes x CH chunks x VEC floats cover one block of G*CH*VEC feature
-// columns (blockIdx.y selects the block).  Rows that keep more than long_k
-// entries are left to the long-row part and not stored here.
-// ---------------------------------------------------------------------------
-template <int G, int CH, int VEC, bool ALIGNED, bool BACKWARD>
-__device__ __forceinline__ void row_block(const Args& a, uint32_t vb, uint2* lds)
-{
-    constexpr int LOG_G = ilog2(G);
-    using P = Pack<VEC, ALIGNED>;
-
-    const int lane = threadIdx.x & (kWaveSize - 1);
-    const int wave = threadIdx.x >> 6;
-    const int logR = a.logR;
-    const int team = kWaveSize >> logR;          // lanes per row
-    const int rs = lane >> (6 - logR);           // row slot inside the wave
-    const int t = lane & (team - 1);             // lane inside the team
-    const int e = t >> LOG_G;                    // edge slot
-    const int l = t & (G - 1);                   // column lane
-    const int E = team >> LOG_G;                 // edge slots per row (>= 1)
-    const int T = kTileSlots >> logR;            // tile slots per row
-    uint2* tile = lds + wave * kWaveTileStride + rs * (T + 1);
-
-    const int64_t r = ((((int64_t)vb * kWavesPerBlock) + wave) << logR) + rs;
-    const bool rvalid = r < a.N;
-    int32_t base = 0, n = 0;
-    if (rvalid) {
-        base = a.rowptr[r];
-        n = a.rowptr[r + 1] - base;
-    }
-    const int k_row = kept_count(a.mode, n, a.W);
-    const bool is_long = k_row > a.long_k;       // summed by the long-row part
-    const int k = is_long ? 0 : k_row;
-
-    LaneCols<G, CH, VEC, ALIGNED> cols;
-    cols.init(blockIdx.y * (G * CH * VEC), l, a.F);
-
-    RowSampler sampler;
-    sampler.init(a.mode, a.seed, r, (uint32_t)n, (uint32_t)a.W, (uint32_t)t, (uint32_t)team);
-
-    if (BACKWARD) {
-        // transposed product: a.X is the upstream gradient, a.Y the (zeroed) output
-        P dy[CH];
-        if (k > 0) load_row_chunks<G, CH, VEC, ALIGNED>(a, r, n, k_row, cols, dy);
-        for (int t0 = 0; t0 < k; t0 += T) {
-            const int count = min(k - t0, T);
-            stage_tile(sampler, t, team, count, base, a.colidx, a.vals, tile);
-            wave_lds_fence();
-            scatter_tile<G, CH, VEC, ALIGNED>(tile, count, e, E, a.Y, a.ldy, cols, dy);
-            wave_lds_fence();
-        }
-        return;
-    }
-
-    P acc[CH];
-#pragma unroll
-    for (int ch = 0; ch < CH; ++ch) acc[ch].zero();
-
-    for (int t0 = 0; t0 < k; t0 += T) {
-        const int count = min(k - t0, T);
-        stage_tile(sampler, t, team, count, base, a.colidx, a.vals, tile);
-        wave_lds_fence();
-        consume_tile<G, CH, VEC, ALIGNED>(tile, count, e, E, a.X, a.ldx, cols, acc);
-        wave_lds_fence();
-    }
-
-    // ---- sum the E edge slots of each row, store ----------------------------
-    for (int m = G; m < team; m <<= 1) {
-#pragma unroll
-        for (int ch = 0; ch < CH; ++ch) acc[ch].add_xor(m);
-    }
-    if (rvalid && !is_long && e == 0) {
-        float* y = a.Y + r * (int64_t)a.ldy;
-        if (a.norm != ES_NORM_NONE) {
-            const float f = row_factor(a.norm, n, k_row);
-#pragma unroll
-            for (int ch = 0; ch < CH; ++ch) acc[ch].scale(f);
-        }
-#pragma unroll
-        for (int ch = 0; ch < CH; ++ch)
-            if (cols.ok[ch]) acc[ch].store(y + cols.off[ch], cols.first[ch]);
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Long-row part.  Workgroup (bx, by) scans rows [bx*1024, bx*1024+1024) for rows
-// that keep more than long_k entries, numbers their 256-slot segments with a
-// prefix sum in LDS, and its 4 waves take segments gw, gw + 4*kLongSplit, ...
-// (gw = by*4 + wave).  A segment is one pass of Algorithm 1 with a whole wave on
-// the row; its partial sums are added to Y (zeroed beforehand by
-// es_zero_long_rows_kernel) with fp32 atomics, so the summation order across
-// segments is not fixed.
-// ---------------------------------------------------------------------------
-struct LongScratch {
-    int seg_end[kLongScanRows];                  // inclusive prefix sum of segment counts
-    int wave_total[kWavesPerBlock];
-};
-
-template <int G, int CH, int VEC, bool ALIGNED, bool BACKWARD>
-__device__ __forceinline__ void long_block(const Args& a, uint32_t bx, uint32_t by, uint2* lds,
-                                           LongScratch& sc)
-{
-    constexpr int LOG_G = ilog2(G);
-    constexpr int kRowsPerThread = kLongScanRows / kBlockThreads;
-    using P = Pack<VEC, ALIGNED>;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWaveSize - 1);
-    const int wave = tid >> 6;
-    const int64_t row0 = (int64_t)bx * kLongScanRows;
-
-    // thread tid owns rows row0 + tid*kRowsPerThread + i (consecutive, so the
-    // prefix order is the row order)
-    int nseg[kRowsPerThread];
-    int mine = 0;
-#pragma unroll
-    for (int i = 0; i < kRowsPerThread; ++i) {
-        const int64_t r = row0 + tid * kRowsPerThread + i;
-        nseg[i] = 0;
-        if (r < a.N) {
-            const int n = a.rowptr[r + 1] - a.rowptr[r];
-            const int k = kept_count(a.mode, n, a.W);
-            if (k > a.long_k) nseg[i] = (k + kLongSeg - 1) / kLongSeg;
-        }
-        mine += nseg[i];
-    }
-    int incl = mine;                             // inclusive scan inside the wave
-#pragma unroll
-    for (int d = 1; d < kWaveSize; d <<= 1) {
-        const int up = __shfl_up(incl, d, kWaveSize);
-        if (lane >= d) incl += up;
-    }
-    if (lane == kWaveSize - 1) sc.wave_total[wave] = incl;
-    __syncthreads();
-    int before = incl - mine;
-    for (int w = 0; w < wave; ++w) before += sc.wave_total[w];
-#pragma unroll
-    for (int i = 0; i < kRowsPerThread; ++i) {
-        before += nseg[i];
-        sc.seg_end[tid * kRowsPerThread + i] = before;
-    }
-    __syncthreads();
-    const int total = sc.seg_end[kLongScanRows - 1];
-    if (total == 0) return;
-
-    const int e = lane >> LOG_G;
-    const int l = lane & (G - 1);
-    constexpr int E = kWaveSize / G;
-    uint2* tile = lds + wave * kWaveTileStride;
-    LaneCols<G, CH, VEC, ALIGNED> cols;
-    cols.init(blockIdx.y * (G * CH * VEC), l, a.F);
-
-    const int gw = by * kWavesPerBlock + wave;
-    for (int task = gw; task < total; task += kLongSplit * kWavesPerBlock) {
-        int lo = 0, hi = kLongScanRows - 1;      // first row whose prefix exceeds task
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (sc.seg_end[mid] > task) hi = mid; else lo = mid + 1;
-        }
-        const int seg = task - (lo ? sc.seg_end[lo - 1] : 0);
-        const int64_t r = row0 + lo;
-        const int32_t base = a.rowptr[r];
-        const int n = a.rowptr[r + 1] - base;
-        const int k = kept_count(a.mode, n, a.W);
-        const int t0 = seg * kLongSeg;
-        const int count = min(k - t0, kLongSeg);
-
-        RowSampler sampler;
-        sampler.init(a.mode, a.seed, r, (uint32_t)n, (uint32_t)a.W, (uint32_t)(t0 + lane), kWaveSize);
-        stage_tile(sampler, lane, kWaveSize, count, base, a.colidx, a.vals, tile);
-        wave_lds_fence();
-        if (BACKWARD) {
-            P dy[CH];
-            load_row_chunks<G, CH, VEC, ALIGNED>(a, r, n, k, cols, dy);
-            scatter_tile<G, CH, VEC, ALIGNED>(tile, count, e, E, a.Y, a.ldy, cols, dy);
-            wave_lds_fence();
-            continue;
-        }
-        P acc[CH];
-#pragma unroll
-        for (int ch = 0; ch < CH; ++ch) acc[ch].zero();
-        consume_tile<G, CH, VEC, ALIGNED>(tile, count, e, E, a.X, a.ldx, cols, acc);
-        wave_lds_fence();
-#pragma unroll
-        for (int m = G; m < kWaveSize; m <<= 1) {
-#pragma unroll
-            for (int ch = 0; ch < CH; ++ch) acc[ch].add_xor(m);
-        }
-        if (e == 0) {
-            float* y = a.Y + r * (int64_t)a.ldy;
-            if (a.norm != ES_NORM_NONE) {
-                const float f = row_factor(a.norm, n, k);
-#pragma unroll
-                for (int ch = 0; ch < CH; ++ch) acc[ch].scale(f);
-            }
-#pragma unroll
-            for (int ch = 0; ch < CH; ++ch)
-                if (cols.ok[ch]) acc[ch].atomic_add(y + cols.off[ch], cols.first[ch]);
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------
-// The fused kernel.  The first a.long_blocks workgroups (dispatched first, so
-// the splitting of long rows overlaps the bulk of the rows) run the long-row
-// part; the rest run the row part, remapped so that each XCD (hardware deals
-// workgroup b to XCD b % 8; long_blocks is a multiple of 8) walks one
-// contiguous range of rows.
-// ---------------------------------------------------------------------------
-template <int G, int CH, int VEC, bool ALIGNED, bool BACKWARD>
-__global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
-{
-    __shared__ uint2 lds[kWavesPerBlock * kWaveTileStride];
-    __shared__ LongScratch long_scratch;
-
-    if (blockIdx.x < a.long_blocks) {
-        long_block<G, CH, VEC, ALIGNED, BACKWARD>(a, blockIdx.x / kLongSplit, blockIdx.x % kLongSplit,
-                                                  lds, long_scratch);
-        return;
-    }
-    const uint32_t b = blockIdx.x - a.long_blocks;
-    const uint32_t vb = (b % kNumXcd) * a.blocks_per_xcd + b / kNumXcd;
-    if (vb >= a.nblocks) return;
-    row_block<G, CH, VEC, ALIGNED, BACKWARD>(a, vb, lds);
-}
-
-// Zero-fills an [N x F] matrix with row stride ld (the transposed product
-// accumulates into its output with atomics).
-__global__ void __launch_bounds__(kBlockThreads)
-es_fill_zero_kernel(float* __restrict__ out, int64_t N, int32_t F, int32_t ld)
-{
-    const int64_t total = N * (int64_t)F;
-    for (int64_t i = (int64_t)blockIdx.x * kBlockThreads + threadIdx.x; i < total;
-         i += (int64_t)gridDim.x * kBlockThreads) {
-        const int64_t r = i / F;
-        out[r * ld + (i - r * F)] = 0.0f;
-    }
-}
-
-// Zeroes Y for the rows the long-row part will accumulate into with atomics.
-// One thread per row; such rows are rare by construction of long_k.
-__global__ void __launch_bounds__(kBlockThreads) es_zero_long_rows_kernel(const Args a)
-{
-    const int64_t r = (int64_t)blockIdx.x * kBlockThreads + threadIdx.x;
-    if (r >= a.N) return;
-    const int n = a.rowptr[r + 1] - a.rowptr[r];
-    if (kept_count(a.mode, n, a.W) <= a.long_k) return;
-    float* y = a.Y + r * (int64_t)a.ldy;
-    for (int c = 0; c < a.F; ++c) y[c] = 0.0f;
-}
-
-// ---------------------------------------------------------------------------
-// Sampler export: identical team / tile schedule, sink writes CSR positions.
-// logR < 0 selects the long-row schedule instead: a whole wave per row, one
-// freshly initialised sampler per kLongSeg-slot segment.
-// ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(kBlockThreads)
-es_sample_edges_kernel(const int32_t* __restrict__ rowptr, int64_t N, int32_t W, int32_t mode,
-                       uint64_t seed, int32_t logR, int32_t* __restrict__ pos,
-                       int32_t* __restrict__ cnt)
-{
-    const int lane = threadIdx.x & (kWaveSize - 1);
-    const int wave = threadIdx.x >> 6;
-    const bool segmented = logR < 0;
-    if (segmented) logR = 0;
-    const int team = kWaveSize >> logR;
-    const int rs = lane >> (6 - logR);
-    const int t = lane & (team - 1);
-    const int T = segmented ? kLongSeg : (kTileSlots >> logR);
-    const int64_t r = ((((int64_t)blockIdx.x * kWavesPerBlock) + wave) << logR) + rs;
-    if (r >= N) return;
-    const int32_t base = rowptr[r];
-    const int32_t n = rowptr[r + 1] - base;
-    const int k = min(n, W);
-
-    RowSampler sampler;
-    sampler.init(mode, seed, r, (uint32_t)n, (uint32_t)W, (uint32_t)t, (uint32_t)team);
-    int32_t* out = pos + r * (int64_t)W;
-    for (int t0 = 0; t0 < k; t0 += T) {
-        const int count = min(k - t0, T);
-        if (segmented)
-            sampler.init(mode, seed, r, (uint32_t)n, (uint32_t)W, (uint32_t)(t0 + t), (uint32_t)team);
-        sample_tile(sampler, t, team, count,
-                    [&](int slot, uint32_t entry) { out[t0 + slot] = base + (int32_t)entry; });
-    }
-    for (int i = k + t; i < W; i += team) out[i] = -1;
-    if (t == 0) cnt[r] = k;
-}
-
-// ---------------------------------------------------------------------------
-// Materialised sampled graph (the pre-sampled input of Section 5.6): row
-// pointers of the kept counts by a three-step in-place scan, then the sampled
-// (column, value) pairs in slot order.
-// ---------------------------------------------------------------------------
-constexpr int kScanRows = 1024;                       // rows per scan workgroup
-constexpr int kScanPerThread = kScanRows / kBlockThreads;
-
-// Step 1: out[r+1] = inclusive prefix, inside the row's 1024-row block, of the
-// kept counts k_r (rowptr given) or of the counts already stored in out[r+1]
-// (rowptr == nullptr; each thread reads its own entries before it writes them).
-__global__ void __launch_bounds__(kBlockThreads)
-es_kept_scan_local_kernel(const int32_t* __restrict__ rowptr, int64_t N, int32_t W, int32_t mode,
-                          int32_t* out)
-{
-    __shared__ int wave_total[kWavesPerBlock];
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWaveSize - 1);
-    const int wave = tid >> 6;
-    const int64_t r0 = (int64_t)blockIdx.x * kScanRows + tid * kScanPerThread;
-    int k[kScanPerThread];
-    int mine = 0;
-#pragma unroll
-    for (int i = 0; i < kScanPerThread; ++i) {
-        const int64_t r = r0 + i;
-        k[i] = 0;
-        if (r < N) k[i] = rowptr ? kept_count(mode, rowptr[r + 1] - rowptr[r], W) : out[r + 1];
-        mine += k[i];
-    }
-    int incl = mine;
-#pragma unroll
-    for (int d = 1; d < kWaveSize; d <<= 1) {
-        const int up = __shfl_up(incl, d, kWaveSize);
-        if (lane >= d) incl += up;
-    }
-    if (lane == kWaveSize - 1) wave_total[wave] = incl;
-    __syncthreads();
-    int run = incl - mine;
-    for (int w = 0; w < wave; ++w) run += wave_total[w];
-#pragma unroll
-    for (int i = 0; i < kScanPerThread; ++i) {
-        run += k[i];
-        if (r0 + i < N) out[r0 + i + 1] = run;
-    }
-    if (blockIdx.x == 0 && tid == 0) out[0] = 0;
-}
-
-// Step 2 (one workgroup): turn the block totals, stored at each block's last
-// row, into global inclusive prefixes.
-__global__ void __launch_bounds__(kBlockThreads)
-es_kept_scan_blocks_kernel(int64_t N, int32_t* __restrict__ out)
-{
-    __shared__ int wave_total[kWavesPerBlock];
-    __shared__ int carry_s;
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWaveSize - 1);
-    const int wave = tid >> 6;
-    const int64_t nblocks = (N + kScanRows - 1) / kScanRows;
-    if (tid == 0) carry_s = 0;
-    __syncthreads();
-    for (int64_t b0 = 0; b0 < nblocks; b0 += kBlockThreads) {
-        const int64_t b = b0 + tid;
-        const int64_t last = min((b + 1) * (int64_t)kScanRows, N);   // index of the block's total
-        const int v = (b < nblocks) ? out[last] : 0;
-        int incl = v;
-#pragma unroll
-        for (int d = 1; d < kWaveSize; d <<= 1) {
-            const int up = __shfl_up(incl, d, kWaveSize);
-            if (lane >= d) incl += up;
-        }
-        if (lane == kWaveSize - 1) wave_total[wave] = incl;
-        __syncthreads();
-        int run = incl + carry_s;
-        for (int w = 0; w < wave; ++w) run += wave_total[w];
-        if (b < nblocks) out[last] = run;
-        __syncthreads();
-        if (tid == kBlockThreads - 1) carry_s = run;
-        __syncthreads();
-    }
-}
-
-// Step 3: add the previous block's global prefix to every entry of a block
-// except its last (already global).
-__global__ void __launch_bounds__(kBlockThreads)
-es_kept_scan_add_kernel(int64_t N, int32_t* __restrict__ out)
-{
-    const int64_t b = blockIdx.x + 1;                 // block 0 needs no offset
-    const int offset = out[b * kScanRows];
-    const int64_t last = min((b + 1) * (int64_t)kScanRows, N);
-    for (int64_t i = b * kScanRows + 1 + threadIdx.x; i < last; i += kBlockThreads) out[i] += offset;
-}
-
-// One team of 64/R lanes per row, same sampler walk as stage 1 of the fused kernel.
-__global__ void __launch_bounds__(kBlockThreads)
-es_materialize_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
-                      const float* __restrict__ vals, int64_t N, int32_t W, int32_t mode,
-                      uint64_t seed, int32_t logR, const int32_t* __restrict__ out_rowptr,
-                      int32_t* __restrict__ out_colidx, float* __restrict__ out_vals)
-{
-    const int lane = threadIdx.x & (kWaveSize - 1);
-    const int wave = threadIdx.x >> 6;
-    const int team = kWaveSize >> logR;
-    const int rs = lane >> (6 - logR);
-    const int t = lane & (team - 1);
-    const int T = kTileSlots >> logR;
-    const int64_t r = ((((int64_t)blockIdx.x * kWavesPerBlock) + wave) << logR) + rs;
-    if (r >= N) return;
-    const int32_t base = rowptr[r];
-    const int32_t n = rowptr[r + 1] - base;
-    const int k = kept_count(mode, n, W);
-    const int64_t obase = out_rowptr[r];
-
-    RowSampler sampler;
-    sampler.init(mode, seed, r, (uint32_t)n, (uint32_t)W, (uint32_t)t, (uint32_t)team);
-    for (int t0 = 0; t0 < k; t0 += T) {
-        const int count = min(k - t0, T);
-        sample_tile(sampler, t, team, count, [&](int slot, uint32_t entry) {
-            const int64_t p = (int64_t)base + entry;
-            out_colidx[obase + t0 + slot] = colidx[p];
-            out_vals[obase + t0 + slot] = vals ? vals[p] : 1.0f;
-        });
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Transposed sampled graph (the sampled graph in CSC form): count the kept
-// entries per column, scan, then drop every entry into its column's segment
-// through a per-column cursor.  Entries of one column arrive in no fixed order.
-// ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(kBlockThreads) es_fill_int_kernel(int32_t* out, int64_t n, int32_t v)
-{
-    for (int64_t i = (int64_t)blockIdx.x * kBlockThreads + threadIdx.x; i < n;
-         i += (int64_t)gridDim.x * kBlockThreads)
-        out[i] = v;
-}
-
-__global__ void __launch_bounds__(kBlockThreads)
-es_copy_int_kernel(const int32_t* __restrict__ in, int32_t* __restrict__ out, int64_t n)
-{
-    for (int64_t i = (int64_t)blockIdx.x * kBlockThreads + threadIdx.x; i < n;
-         i += (int64_t)gridDim.x * kBlockThreads)
-        out[i] = in[i];
-}
-
-// FILL == false: out_ptr[c + 1] += 1 per kept entry with column c.
-// FILL == true : the entry goes to position out_end[c]++ of out_idx / out_vals
-//                (value times the row factor).
-template <bool FILL>
-__global__ void __launch_bounds__(kBlockThreads)
-es_transpose_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
-                    const float* __restrict__ vals, int64_t N, int32_t W, int32_t mode, uint64_t seed,
-                    int32_t norm, int32_t logR, int32_t* out_ptr, int32_t* out_end,
-                    int32_t* __restrict__ out_idx, float* __restrict__ out_vals)
-{
-    const int lane = threadIdx.x & (kWaveSize - 1);
-    const int wave = threadIdx.x >> 6;
-    const int team = kWaveSize >> logR;
-    const int rs = lane >> (6 - logR);
-    const int t = lane & (team - 1);
-    const int T = kTileSlots >> logR;
-    const int64_t r = ((((int64_t)blockIdx.x * kWavesPerBlock) + wave) << logR) + rs;
-    if (r >= N) return;
-    const int32_t base = rowptr[r];
-    const int32_t n = rowptr[r + 1] - base;
-    const int k = kept_count(mode, n, W);
-    const float f = row_factor(norm, n, k);
-
-    RowSampler sampler;
-    sampler.init(mode, seed, r, (uint32_t)n, (uint32_t)W, (uint32_t)t, (uint32_t)team);
-    for (int t0 = 0; t0 < k; t0 += T) {
-        const int count = min(k - t0, T);
-        sample_tile(sampler, t, team, count, [&](int, uint32_t entry) {
-            const int64_t p = (int64_t)base + entry;
-            const int32_t c = colidx[p];
-            if (!FILL) {
-                atomicAdd(out_ptr + c + 1, 1);
-            } else {
-                const int32_t pos = atomicAdd(out_end + c, 1);
-                out_idx[pos] = (int32_t)r;
-                out_vals[pos] = f * (vals ? vals[p] : 1.0f);
-            }
-        });
-    }
-}
 
 // ---------------------------------------------------------------------------
 // host side
