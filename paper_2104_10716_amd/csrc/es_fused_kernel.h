@@ -247,15 +247,25 @@ es_fill_zero_kernel(float* __restrict__ out, int64_t N, int32_t F, int32_t ld)
 }
 
 // Zeroes Y for the rows the long-row part will accumulate into with atomics.
-// One thread per row; such rows are rare by construction of long_k.
+// Each lane tests one row; the wave then clears the flagged rows together, 64
+// consecutive floats per store instruction.
 __global__ void __launch_bounds__(kBlockThreads) es_zero_long_rows_kernel(const Args a)
 {
+    const int lane = threadIdx.x & (kWaveSize - 1);
     const int64_t r = (int64_t)blockIdx.x * kBlockThreads + threadIdx.x;
-    if (r >= a.N) return;
-    const int n = a.rowptr[r + 1] - a.rowptr[r];
-    if (kept_count(a.mode, n, a.W) <= a.long_k) return;
-    float* y = a.Y + r * (int64_t)a.ldy;
-    for (int c = 0; c < a.F; ++c) y[c] = 0.0f;
+    bool is_long = false;
+    if (r < a.N) {
+        const int n = a.rowptr[r + 1] - a.rowptr[r];
+        is_long = kept_count(a.mode, n, a.W) > a.long_k;
+    }
+    unsigned long long flagged = __ballot(is_long);
+    const int64_t wave_row0 = r - lane;
+    while (flagged) {
+        const int src = __ffsll((long long)flagged) - 1;
+        flagged &= flagged - 1;
+        float* y = a.Y + (wave_row0 + src) * (int64_t)a.ldy;
+        for (int c = lane; c < a.F; c += kWaveSize) y[c] = 0.0f;
+    }
 }
 
 }  // namespace
