@@ -491,6 +491,12 @@ def test_config3_social_like_full_size(es):
         for mode in ("bucket", "fastrand"):
             check_edges(d, W, mode, 0)
             _say(f"cfg3 {mode} W={W}: edge lists identical")
+    # seeded rotation, and the long-row sampler schedule, on every row
+    check_edges(d, 64, "fastrand", 0xC0FFEE123456789)
+    check_edges(d, 64, "fastrand", 3, rows_per_wave=-1)
+    check_edges(d, 300, "fastrand", 3, rows_per_wave=-1)
+    worst = check_against_oracle(d, 64, "fastrand", 0xC0FFEE123456789, rows=rows, what="cfg3 fastrand W=64 seeded")
+    _say(f"cfg3 fastrand W=64 with a 60-bit seed: edge lists identical, max normalised error {worst:.2e}")
     # the widths the paper needs for Bucket on its densest graph (S = 1792, 2304):
     # several LDS tiles per row, and rows above the long-row threshold
     for W in (1792, 2304):
