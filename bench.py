@@ -33,9 +33,9 @@ HBM_PEAK_GBPS = 8000.0
 # step) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a copy
 # kernel of known size; filled in from the summaries under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    2: 818075303,      # profiles/es_spmm_config2_sweep.md
-    3: 7115403684,     # profiles/es_spmm_config3_sweep.md
-    4: 31021343091,    # profiles/es_spmm_config4_sweep.md
+    2: 818073543,      # profiles/es_spmm_config2_sweep.md
+    3: 7114890775,     # profiles/es_spmm_config3_sweep.md
+    4: 31021331251,    # profiles/es_spmm_config4_sweep.md
 }
 
 CONFIG_TEXT = {
