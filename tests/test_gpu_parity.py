@@ -348,6 +348,33 @@ def test_hip_graph_capture_and_replay(es):
     es.es_spmm_set_long_row_threshold(0)
 
 
+def test_concurrent_streams(es):
+    """Calls on two streams at once (different graphs, interleaved launches)
+    give what the same calls give one after the other: the library keeps no
+    per-call state and every kernel works only on its arguments."""
+    import torch
+    from gpu_util import DeviceCSR
+    ga = DeviceCSR(*_random_graph(20_000, 30.0, seed=51, F=64))
+    gb = DeviceCSR(*_random_graph(15_000, 8.0, seed=52, F=128))
+    cases = [(ga, 16, "fastrand", 4), (gb, 0, "full", 0), (ga, 0, "full", 0), (gb, 5, "bucket", 0),
+             (ga, 100, "fastrand", 9), (gb, 64, "fastrand", 2)]
+    serial = [d.run(W, mode, seed) for d, W, mode, seed in cases]
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = [torch.full((d.N, d.F), float("nan"), dtype=torch.float32, device="cuda:0") for d, *_ in cases]
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for i, (d, W, mode, seed) in enumerate(cases):
+            with torch.cuda.stream(s1 if i % 2 == 0 else s2):
+                es.es_spmm(d.rowptr, d.colidx, d.vals, d.X, outs[i], W, mode, seed)
+    s1.synchronize()
+    s2.synchronize()
+    for i, (d, W, mode, seed) in enumerate(cases):
+        if mode == "full":
+            assert torch.allclose(outs[i], serial[i], rtol=1e-4, atol=1e-5), i
+        else:
+            assert torch.equal(outs[i], serial[i]), i
+
+
 def test_determinism_across_launches(es):
     """Same inputs, same launch shape: bit-identical Y and edge lists (the
     sampler is static for a given seed, Section 6.2).  Full mode is
