@@ -36,6 +36,8 @@ MEASURED_TRAFFIC_BYTES = {
     2: 818073543,      # profiles/es_spmm_config2_sweep.md
     3: 7114890775,     # profiles/es_spmm_config3_sweep.md
     4: 31021331251,    # profiles/es_spmm_config4_sweep.md
+    (5, 41): 12565809080,   # profiles/es_spmm_config5_F41.md
+    (5, 256): 48857946425,  # profiles/es_spmm_config5_F256.md
 }
 
 CONFIG_TEXT = {
@@ -150,6 +152,7 @@ def cpu_baseline_rows(dw, calls, target_seconds=20.0):
     import numpy as np
     import oracle
     w = dw.w
+    Xh = w.X if dw.X.shape == w.X.shape else dw.X.cpu().numpy()
     work = sum(dw.nnz_kept(m, W) for m, W in calls) * dw.F
     frac = min(1.0, target_seconds * 1.0e9 / max(work, 1))     # ~1 G fp64 FMA per second assumed
     nrows = max(1, int(dw.N * frac))
@@ -157,7 +160,7 @@ def cpu_baseline_rows(dw, calls, target_seconds=20.0):
     t0 = time.perf_counter()
     total_bytes = 0
     for mode, W in calls:
-        oracle.spmm(w.rowptr, w.colidx, w.vals, w.X, dw.F, W, mode, 0, rows=rows, want_denom=False)
+        oracle.spmm(w.rowptr, w.colidx, w.vals, Xh, dw.F, W, mode, 0, rows=rows, want_denom=False)
         kept = int((dw.deg[rows] if mode == "full" else np.minimum(dw.deg[rows], W)).sum())
         total_bytes += algorithmic_bytes(nrows, kept, dw.F)
     dt = time.perf_counter() - t0
@@ -171,7 +174,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, choices=(2, 3, 4))
+    ap.add_argument("--config", type=int, default=2, choices=(2, 3, 4, 5))
+    ap.add_argument("--feature-width", type=int, default=41, choices=(41, 256),
+                    help="config 5 only: which SpMM stage of the 2-layer GCN forward to time")
     ap.add_argument("--main-only", action="store_true",
                     help="only the timed sweep of --config (what the rocprofv3 summaries profile)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -192,10 +197,17 @@ def main() -> int:
     dev = torch.device("cuda:0")
 
     t0 = time.perf_counter()
-    w = make_workload(args.config)
+    w = make_workload(3 if args.config == 5 else args.config)
     log(f"config {args.config}: N={w.N} nnz={w.nnz} F={w.F} generated in {time.perf_counter() - t0:.1f}s")
-    dw = DeviceWorkload(w, dev)
-    calls = dw.calls(w.Ws)
+    if args.config == 5:
+        dw = gcn_stage_workload(w, dev, args.feature_width)
+        calls = dw.calls((64,))
+        workload_text = (f"configs[4] 2-layer GCN forward on the config-3 graph, SpMM stage at "
+                         f"F={args.feature_width} (row stride {args.feature_width})")
+    else:
+        dw = DeviceWorkload(w, dev)
+        calls = dw.calls(w.Ws)
+        workload_text = CONFIG_TEXT[args.config]
     step_bytes = sum(algorithmic_bytes(dw.N, dw.nnz_kept(m, W), dw.F) for m, W in calls)
     step_flops = sum(2 * dw.nnz_kept(m, W) * dw.F for m, W in calls)
 
@@ -242,12 +254,13 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "gflops": round(step_flops / (ms_per_step * 1e6), 1),
-        "config": {"workload": CONFIG_TEXT[args.config], "N": dw.N, "nnz": dw.nnz, "F": dw.F,
-                   "W": list(w.Ws), "modes": ["bucket", "fastrand", "full"], "seed": 0,
+        "config": {"workload": workload_text, "N": dw.N, "nnz": dw.nnz, "F": dw.F,
+                   "W": sorted({W for _, W in calls if W}), "modes": ["bucket", "fastrand", "full"], "seed": 0,
                    "calls_per_step": len(calls)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((5, args.feature_width) if args.config == 5
+                                                          else args.config),
                      "kernel": "es_spmm_kernel", "launch_ms": round(kernel_ms, 5),
                      "bytes_per_launch": int(bytes_per_launch)},
     }
@@ -420,6 +433,21 @@ def backward_table(dw, dev, cases):
             f"+ pull {t_pull:.3f} ms | forward {t_fwd:.3f} ms")
         del bufs, ptr, idx, val
     return out
+
+
+def gcn_stage_workload(w3, dev, F):
+    """DeviceWorkload for one SpMM stage of configs[4]: X = X0 W1 (F=256) or
+    X = relu(ES-SpMM(A, X0 W1)) W2 (F=41; first stage run with FastRand, W=64)."""
+    import torch
+    from workloads import gcn_operands
+    X0h, W1h, W2h = gcn_operands(w3.N)
+    Z1 = torch.from_numpy(X0h).to(dev) @ torch.from_numpy(W1h).to(dev)
+    d1 = DeviceWorkload(w3, dev, X=Z1, F=256)
+    if F == 256:
+        return d1
+    d1.launch("fastrand", 64)
+    Z2 = torch.relu(d1.Y) @ torch.from_numpy(W2h).to(dev)
+    return DeviceWorkload(w3, dev, X=Z2.contiguous(), F=41)
 
 
 def gcn_feature_sweep(dw3, dev, flush):
