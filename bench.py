@@ -142,9 +142,18 @@ def cpu_baseline(dw, calls, min_seconds=10.0, max_steps=200):
         dt = time.perf_counter() - t0
         if dt >= min_seconds or steps >= max_steps:
             break
-    return {"value": round(steps * step_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.threads(),
-            "kind": "oracle", "seconds": round(dt, 2),
-            "sample": f"{steps} whole steps (every call of the sweep, all rows), fp64 accumulation"}
+    out = {"value": round(steps * step_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.threads(),
+           "kind": "oracle", "seconds": round(dt, 2),
+           "sample": f"{steps} whole steps (every call of the sweep, all rows), fp64 accumulation"}
+    all_threads = oracle.threads()
+    oracle.set_threads(1)                    # the same oracle on one core, one step
+    t0 = time.perf_counter()
+    for mode, W in calls:
+        oracle.spmm(w.rowptr, w.colidx, w.vals, w.X, dw.F, W, mode, 0, want_denom=False)
+    dt1 = time.perf_counter() - t0
+    oracle.set_threads(all_threads)
+    out["single_core_value"] = round(step_bytes / dt1 / 1e9, 3)
+    return out
 
 
 def cpu_baseline_rows(dw, calls, target_seconds=20.0):

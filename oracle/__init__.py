@@ -70,6 +70,8 @@ def _load():
     lib.es_oracle_splitmix64_next.argtypes = [ctypes.POINTER(ctypes.c_uint64)]
     lib.es_oracle_threads.restype = ctypes.c_int
     lib.es_oracle_threads.argtypes = []
+    lib.es_oracle_set_threads.restype = ctypes.c_int
+    lib.es_oracle_set_threads.argtypes = [ctypes.c_int]
     _lib = lib
     return lib
 
@@ -93,6 +95,11 @@ def _c(a, dtype) -> np.ndarray:
 
 def threads() -> int:
     return int(_load().es_oracle_threads())
+
+
+def set_threads(n: int) -> int:
+    """Thread count of the row loop (timing harness only); returns the count in use."""
+    return int(_load().es_oracle_set_threads(int(n)))
 
 
 def sample_index(mode, seed: int, row: int, i: int, n: int, W: int) -> int:

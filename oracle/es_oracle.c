@@ -261,6 +261,19 @@ int es_oracle_spmm_backward(const int32_t *rowptr, const int32_t *colidx, const 
     return 0;
 }
 
+/* Sets the thread count of the row loop (0 or less: leave as is); returns the
+ * count now in use.  Only the timing harness calls this. */
+int es_oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+    return omp_get_max_threads();
+#else
+    (void)n;
+    return 1;
+#endif
+}
+
 /* Threads the row loop of es_oracle_spmm uses. */
 int es_oracle_threads(void)
 {
