@@ -175,9 +175,19 @@ def test_degenerate_inputs(es):
     e = torch.empty((0, 4), dtype=torch.float32, device="cuda:0")
     es.es_spmm(torch.zeros(1, dtype=torch.int32, device="cuda:0"),
                torch.zeros(0, dtype=torch.int32, device="cuda:0"), None, e, e.clone(), 4, "bucket")
-    # errors surface as exceptions with the status
+    # errors surface as exceptions with the status, and leave the output untouched
     with pytest.raises(es.EsSpmmError):
         d.run(0, "bucket")
+    Yk = torch.full((du.N, du.F), 7.0, dtype=torch.float32, device="cuda:0")
+    for bad in (dict(W=0, mode="fastrand"), dict(W=4, mode=9), dict(W=4, mode="bucket", F=du.F + 1)):
+        with pytest.raises((es.EsSpmmError, ValueError)):
+            es.es_spmm(du.rowptr, du.colidx, du.vals, du.X, Yk, bad["W"], bad["mode"], F=bad.get("F"))
+    with pytest.raises(es.EsSpmmError):
+        es.es_spmm_norm(du.rowptr, du.colidx, du.vals, du.X, Yk, 4, "bucket", 0, 99)
+    with pytest.raises(es.EsSpmmError):
+        es.es_spmm_backward(du.rowptr, du.colidx, du.vals, du.X, Yk, 0, "bucket")
+    torch.cuda.synchronize()
+    assert bool((Yk == 7.0).all())
     # runs on a non-default stream too
     s = torch.cuda.Stream()
     with torch.cuda.stream(s):
