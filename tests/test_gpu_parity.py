@@ -96,6 +96,46 @@ def test_column_slicing_override(es, F):
     es.es_spmm_set_lanes_per_row(0)
 
 
+def test_randomised_shapes(es):
+    """Seeded sweep over random combinations of graph size, degree, F, row
+    strides, W, mode, seed, row factor and the three launch overrides, forward
+    and transposed, each against the oracle."""
+    import torch
+    from gpu_util import DeviceCSR, check_against_oracle, check_backward_against_oracle, check_edges
+    rng = np.random.default_rng(20260101)
+    for case in range(400):
+        n = int(rng.choice([1, 2, 63, 64, 65, 257, 1000, 3001]))
+        avg = float(rng.choice([0.5, 3.0, 20.0, 90.0]))
+        F = int(rng.choice([1, 2, 4, 5, 8, 12, 16, 31, 32, 41, 64, 96, 100, 128, 192, 256, 300, 512, 700]))
+        pad = int(rng.choice([0, 0, 1, 3, 4]))
+        rowptr, colidx, vals, X = _random_graph(n, avg, seed=1000 + case, F=F, ldx=F + pad,
+                                                empty_frac=float(rng.choice([0.0, 0.3])),
+                                                unit_vals=bool(rng.integers(0, 4) == 0))
+        d = DeviceCSR(rowptr, colidx, vals, X, F=F)
+        maxdeg = max(1, int(np.diff(rowptr).max()))
+        mode = str(rng.choice(["full", "bucket", "fastrand", "fastrand"]))
+        W = int(rng.choice([1, 2, 7, 16, 33, max(1, maxdeg - 1), maxdeg, maxdeg + 9]))
+        seed = int(rng.choice([0, 1, 2 ** 63 + 12345]))
+        norm = str(rng.choice(["none", "none", "mean", "rsqrt", "rescale", "inv_degree"]))
+        rpw = int(rng.choice([0, 0, 1, 2, 16, 64]))
+        thr = int(rng.choice([0, 0, 1, 3, 40]))
+        lanes = int(rng.choice([0, 0, 0, 4, 16]))
+        es.es_spmm_set_rows_per_wave(rpw)
+        es.es_spmm_set_long_row_threshold(thr)
+        es.es_spmm_set_lanes_per_row(lanes)
+        what = (f"case {case}: n={n} avg={avg} F={F} ld={F + pad} {mode} W={W} seed={seed} norm={norm} "
+                f"rpw={rpw} thr={thr} lanes={lanes}")
+        _say(what)
+        ldy = F + int(rng.choice([0, 0, 2, 4]))
+        check_against_oracle(d, W, mode, seed, ldy=ldy, norm=norm, what=what)
+        check_backward_against_oracle(d, W, mode, seed, norm, what="backward " + what)
+        if mode != "full":
+            check_edges(d, W, mode, seed, int(rng.choice([0, 1, 4, -1])), what="edges " + what)
+    es.es_spmm_set_rows_per_wave(0)
+    es.es_spmm_set_long_row_threshold(0)
+    es.es_spmm_set_lanes_per_row(0)
+
+
 def test_long_rows_span_several_tiles(es):
     """Rows far longer than one LDS tile (full mode and W above the tile),
     including lengths that are multiples of 577 where the multiplier changes."""
