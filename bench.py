@@ -278,6 +278,7 @@ def main() -> int:
         flush = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device=dev)   # 1 GiB
         flush.zero_()
         result["calls"] = per_call_table(dw, calls, 20, flush, 5)
+        result["vendor_csr_spmm_ms"] = vendor_csr_spmm_ms(dw)
         if not args.no_cpu_baseline:
             result["cpu_baseline"] = (cpu_baseline(dw, calls) if args.config == 2
                                       else cpu_baseline_rows(dw, calls))
@@ -293,7 +294,8 @@ def main() -> int:
             log(f"config {cfg}: N={w.N} nnz={w.nnz} F={w.F} generated in {time.perf_counter() - t0:.1f}s")
             dw = DeviceWorkload(w, dev)
             rows = per_call_table(dw, dw.calls(w.Ws), 10, flush, 3)
-            extra.append({"workload": CONFIG_TEXT[cfg], "N": dw.N, "nnz": dw.nnz, "F": dw.F, "calls": rows})
+            extra.append({"workload": CONFIG_TEXT[cfg], "N": dw.N, "nnz": dw.nnz, "F": dw.F, "calls": rows,
+                          "vendor_csr_spmm_ms": vendor_csr_spmm_ms(dw)})
             for r in rows:
                 log(f"  cfg{cfg} {r['mode']:8s} W={r['W']:4d}: {r['ms']:.3f} ms  {r['eff_GBps']:.0f} GB/s "
                     f"({100 * r['frac_hbm_peak']:.1f}% of peak)  cold {r['ms_cold']} ms  x{r['speedup_vs_full']} vs full")
@@ -317,6 +319,25 @@ def main() -> int:
 
     print(json.dumps(result), flush=True)
     return 0
+
+
+def vendor_csr_spmm_ms(dw):
+    """Context only: the exact product through torch.sparse.mm on a CSR tensor
+    (the vendor sparse library as PyTorch ships and calls it) -- the role
+    cuSPARSE plays in the paper's tables.  None if that path is unavailable."""
+    import warnings
+    import torch
+    try:
+        with warnings.catch_warnings():
+            warnings.simplefilter("ignore")
+            A = torch.sparse_csr_tensor(dw.rowptr, dw.colidx, dw.vals, size=(dw.N, dw.N))
+            X = dw.X[:, :dw.F].contiguous() if dw.X.shape[1] != dw.F else dw.X
+            t = _time_fn(lambda: torch.sparse.mm(A, X), reps=5, warm=2)
+        log(f"  vendor CSR SpMM via torch.sparse.mm (context): {t:.3f} ms")
+        return round(t, 4)
+    except Exception as exc:                                   # noqa: BLE001 - context figure only
+        log(f"  vendor CSR SpMM unavailable: {exc}")
+        return None
 
 
 def tiny_config1(dev):
