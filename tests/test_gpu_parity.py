@@ -716,3 +716,6 @@ def test_config4_copurchase_like_full_size(es):
             _say(f"cfg4 {mode} W={W}: max normalised error {worst:.2e}")
     check_edges(d, 32, "fastrand", 0)
     _say("cfg4 fastrand W=32: edge lists identical")
+    check_edges(d, 128, "fastrand", 77)
+    check_edges(d, 64, "bucket", 0)
+    _say("cfg4 fastrand W=128 (seeded) and bucket W=64: edge lists identical")
