@@ -177,6 +177,25 @@ int es_spmm_materialize_transposed(const int32_t* rowptr, const int32_t* colidx,
                                    int32_t* out_idx, float* out_vals, void* stream);
 
 /*
+ * es_spmm_validate_csr -- checks on the device what every other entry point
+ * takes on trust (see "Not checked" above); meant to be run once on a graph of
+ * unknown origin, since a bad column id makes es_spmm read outside X.
+ *   report [4] int32 (device), written:
+ *     report[0]  row-pointer faults: pairs with rowptr[r+1] < rowptr[r] or
+ *                outside [0, nnz], plus one each if rowptr[0] != 0 or
+ *                rowptr[N] != nnz
+ *     report[1]  column ids outside [0, N) (only rows with a sound pointer
+ *                pair are inspected)
+ *     report[2]  rows whose column ids are not strictly increasing -- legal,
+ *                but "the first W entries" of ES_BUCKET (Section 4.4) then
+ *                means storage order, not the lowest-numbered neighbours
+ *     report[3]  length of the longest row
+ * The graph is usable when report[0] == 0 and report[1] == 0.
+ */
+int es_spmm_validate_csr(const int32_t* rowptr, const int32_t* colidx, int64_t N, int64_t nnz,
+                         int32_t* report, void* stream);
+
+/*
  * es_spmm_launch_info -- the launch shape es_spmm_norm (backward == 0) or
  * es_spmm_backward (backward != 0) would pick for these sizes, without
  * launching anything and without a GPU.  `aligned16`: both matrices are

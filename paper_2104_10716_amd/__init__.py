@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     es_spmm_set_rows_per_wave,
     es_spmm_status_string,
     es_spmm_tile_slots,
+    es_spmm_validate_csr,
     library_path,
     load_library,
 )

@@ -70,6 +70,8 @@ def load_library():
     lib.es_spmm_materialize_transposed.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int64,
                                                    ctypes.c_int32, ctypes.c_int32, ctypes.c_uint64,
                                                    ctypes.c_int32, vp, vp, vp, vp, vp]
+    lib.es_spmm_validate_csr.restype = ctypes.c_int
+    lib.es_spmm_validate_csr.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int64, vp, vp]
     lib.es_spmm_launch_info.restype = ctypes.c_int
     lib.es_spmm_launch_info.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                         ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
@@ -302,3 +304,19 @@ def es_spmm_materialize_transposed(rowptr, colidx, vals, W: int, mode, seed: int
     if rc != 0:
         raise EsSpmmError(rc, "es_spmm_materialize_transposed")
     return out_ptr, out_end, out_idx, out_vals
+
+
+def es_spmm_validate_csr(rowptr, colidx, report=None, stream=None):
+    """Device-side CSR check; returns the int32[4] report tensor (row-pointer faults,
+    column ids out of range, rows with unsorted columns, longest row)."""
+    import torch
+    lib = load_library()
+    N = rowptr.numel() - 1
+    if report is None:
+        report = torch.empty((4,), dtype=torch.int32, device=rowptr.device)
+    rc = lib.es_spmm_validate_csr(_dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(colidx, torch.int32, "colidx"),
+                                  N, colidx.numel(), _dev_ptr(report, torch.int32, "report"),
+                                  _stream_ptr(stream))
+    if rc != 0:
+        raise EsSpmmError(rc, "es_spmm_validate_csr")
+    return report

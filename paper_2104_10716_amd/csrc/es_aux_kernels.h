@@ -229,6 +229,50 @@ es_transpose_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restric
     }
 }
 
+// ---------------------------------------------------------------------------
+// CSR check: what es_spmm takes on trust (row pointers that start at 0, never
+// decrease and end at nnz; column ids inside [0, N)).  One wave per row; a
+// row's entries are only read when its own pointer pair lies inside [0, nnz].
+// report[0] = bad row-pointer pairs (plus 1 each if rowptr[0] != 0 or
+// rowptr[N] != nnz), report[1] = column ids outside [0, N), report[2] = rows
+// whose column ids are not strictly increasing, report[3] = longest row.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlockThreads)
+es_validate_csr_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+                       int64_t N, int64_t nnz, int32_t* report)
+{
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = threadIdx.x >> 6;
+    const int64_t waves = (int64_t)gridDim.x * kWavesPerBlock;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (rowptr[0] != 0) atomicAdd(report + 0, 1);
+        if ((int64_t)rowptr[N] != nnz) atomicAdd(report + 0, 1);
+    }
+    for (int64_t r = (int64_t)blockIdx.x * kWavesPerBlock + wave; r < N; r += waves) {
+        const int64_t b = rowptr[r], e = rowptr[r + 1];
+        if (b < 0 || e < b || e > nnz) {
+            if (lane == 0) atomicAdd(report + 0, 1);
+            continue;
+        }
+        int bad_col = 0, unsorted = 0;
+        for (int64_t p = b + lane; p < e; p += kWaveSize) {
+            const int32_t c = colidx[p];
+            if (c < 0 || (int64_t)c >= N) ++bad_col;
+            if (p > b && colidx[p - 1] >= c) unsorted = 1;
+        }
+#pragma unroll
+        for (int m = 1; m < kWaveSize; m <<= 1) {
+            bad_col += __shfl_xor(bad_col, m, kWaveSize);
+            unsorted |= __shfl_xor(unsorted, m, kWaveSize);
+        }
+        if (lane == 0) {
+            if (bad_col) atomicAdd(report + 1, bad_col);
+            if (unsorted) atomicAdd(report + 2, 1);
+            atomicMax(report + 3, (int32_t)(e - b));
+        }
+    }
+}
+
 }  // namespace
 
 #endif  // ES_SPMM_AUX_KERNELS_H

@@ -458,6 +458,22 @@ int es_spmm_materialize_transposed(const int32_t* rowptr, const int32_t* colidx,
     return ES_OK;
 }
 
+int es_spmm_validate_csr(const int32_t* rowptr, const int32_t* colidx, int64_t N, int64_t nnz,
+                         int32_t* report, void* stream)
+{
+    if (N < 0 || nnz < 0 || nnz > INT32_MAX || !rowptr || !report) return ES_ERR_INVALID_ARG;
+    if (nnz > 0 && !colidx) return ES_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(es_fill_int_kernel, dim3(1), dim3(kBlockThreads), 0, st, report, (int64_t)4, 0);
+    if (hipGetLastError() != hipSuccess) return ES_ERR_LAUNCH;
+    int64_t blocks = (N + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(es_validate_csr_kernel, dim3((uint32_t)blocks), dim3(kBlockThreads), 0, st, rowptr,
+                       colidx, N, nnz, report);
+    return hipGetLastError() == hipSuccess ? ES_OK : ES_ERR_LAUNCH;
+}
+
 int es_spmm_sample_edges(const int32_t* rowptr, int64_t N, int32_t W, int32_t mode, uint64_t seed,
                          int32_t rows_per_wave, int32_t* pos, int32_t* cnt, void* stream)
 {

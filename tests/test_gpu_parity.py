@@ -398,6 +398,50 @@ def test_hip_graph_capture_and_replay(es):
     es.es_spmm_set_long_row_threshold(0)
 
 
+def test_validate_csr(es):
+    """es_spmm_validate_csr reports exactly the faults planted in a host copy of
+    a sound graph (and reads nothing it should not while doing so)."""
+    import torch
+    rowptr, colidx, _, _ = _random_graph(5000, 12.0, seed=77, F=4, empty_frac=0.1)
+    N = rowptr.shape[0] - 1
+    maxdeg = int(np.diff(rowptr).max())
+
+    def report(rp, ci):
+        out = es.es_spmm_validate_csr(torch.from_numpy(rp).to("cuda:0"), torch.from_numpy(ci).to("cuda:0"))
+        torch.cuda.synchronize()
+        return out.cpu().numpy().tolist()
+
+    assert report(rowptr, colidx) == [0, 0, 0, maxdeg]
+    w = _workload(2)
+    assert report(w.rowptr, w.colidx) == [0, 0, 0, w.max_degree]
+    long_rows = np.nonzero(np.diff(rowptr) >= 3)[0]
+    # column ids out of range, in three rows
+    ci = colidx.copy()
+    for r, bad in zip(long_rows[:3], (-1, N, 2 ** 31 - 1)):
+        ci[rowptr[r] + 1] = bad
+    rep = report(rowptr, ci)
+    assert rep[0] == 0 and rep[1] == 3 and rep[3] == maxdeg
+    # unsorted rows (swap two entries): legal, counted
+    ci = colidx.copy()
+    for r in long_rows[:5]:
+        ci[[rowptr[r], rowptr[r] + 1]] = ci[[rowptr[r] + 1, rowptr[r]]]
+    assert report(rowptr, ci) == [0, 0, 5, maxdeg]
+    # row pointers: one decreasing pair (its two neighbours become faulty pairs), a wrong end, a wrong start
+    rp = rowptr.copy()
+    rp[100] = rp[101] + 5
+    rep = report(rp, colidx)
+    assert rep[0] >= 1 and rep[1] == 0
+    rp = rowptr.copy()
+    rp[-1] += 7                                   # points past the arrays: that row must not be read
+    rep = report(rp, colidx)
+    assert rep[0] == 2                            # rowptr[N] != nnz, and the last pair exceeds nnz
+    rp = rowptr.copy()
+    rp[0] = 1
+    assert report(rp, colidx)[0] >= 1
+    # empty graph
+    assert report(np.zeros(4, dtype=np.int32), np.zeros(0, dtype=np.int32)) == [0, 0, 0, 0]
+
+
 def test_concurrent_streams(es):
     """Calls on two streams at once (different graphs, interleaved launches)
     give what the same calls give one after the other: the library keeps no
