@@ -12,6 +12,8 @@
  * Conventions for every entry point
  *   - All array pointers are DEVICE pointers on the current HIP device, owned by
  *     the caller; the library neither allocates, frees nor retains them.
+ *   - The library keeps no state between calls: no process-wide settings, no
+ *     hidden workspace.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
  *     default stream).  Calls return as soon as the launch is queued; they never
  *     synchronise and never read device memory on the host.
@@ -196,13 +198,58 @@ int es_spmm_validate_csr(const int32_t* rowptr, const int32_t* colidx, int64_t N
                          int32_t* report, void* stream);
 
 /*
- * es_spmm_launch_info -- the launch shape es_spmm_norm (backward == 0) or
- * es_spmm_backward (backward != 0) would pick for these sizes, without
- * launching anything and without a GPU.  `aligned16`: both matrices are
- * 16-byte aligned.  The shape is how Section 4.5's "thread management" maps
- * onto wave64: lanes_per_row x edge_slots lanes form a row's thread group,
- * rows_per_wave such groups share a wavefront.  Honours the two overrides
- * below.  N must be >= 1.
+ * es_launch_opts_t -- per-call launch-shape overrides (Section 4.5 of the paper,
+ * "thread management" and "load balancing": how rows map onto thread groups
+ * and how skewed rows are balanced).  Passed by pointer to the *_ex entry
+ * points and to es_spmm_launch_info; NULL, or a field left 0, means "the
+ * library's own choice".  The struct is read during the call and not retained;
+ * the library keeps no launch state between calls, so concurrent calls with
+ * different options never interact.  No option changes which entries are
+ * sampled; Y differs between settings only by fp32 summation order.
+ */
+typedef struct {
+    int32_t rows_per_wave;       /* rows sharing one wavefront: a power of two in
+                                    [1, 64], lowered when F needs more lanes per row
+                                    (Section 4.2 assigns a thread group per row; the
+                                    group is 64 / rows_per_wave lanes)              */
+    int32_t lanes_per_row;       /* column slicing: cap the lanes spanning the
+                                    feature columns at 4, 8, 16, 32 or 64, so one
+                                    workgroup covers 4 * lanes columns and the rows
+                                    are swept once per column slice (a smaller piece
+                                    of X per sweep; the sampler runs once per slice).
+                                    -1 = never slice.  Ignored by the backward pass */
+    int32_t long_row_threshold;  /* a row keeping more entries than this is cut into
+                                    256-entry segments that several workgroups sum
+                                    with atomic adds (load balance for skewed degree
+                                    distributions); any positive value             */
+    int32_t reserved;            /* must be 0                                       */
+} es_launch_opts_t;
+
+/*
+ * es_spmm_ex -- es_spmm_norm with per-call launch options (`opts` may be NULL).
+ * ES_ERR_INVALID_ARG for an option outside the ranges above.
+ */
+int es_spmm_ex(const int32_t* rowptr, const int32_t* colidx, const float* vals,
+               const float* X, float* Y,
+               int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy,
+               int32_t W, int32_t mode, uint64_t seed, int32_t norm,
+               const es_launch_opts_t* opts, void* stream);
+
+/* es_spmm_backward_ex -- es_spmm_backward with per-call launch options. */
+int es_spmm_backward_ex(const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                        const float* dY, float* dX,
+                        int64_t N, int64_t nnz, int32_t F, int32_t ldy, int32_t ldx,
+                        int32_t W, int32_t mode, uint64_t seed, int32_t norm,
+                        const es_launch_opts_t* opts, void* stream);
+
+/*
+ * es_spmm_launch_info -- the launch shape es_spmm_ex (backward == 0) or
+ * es_spmm_backward_ex (backward != 0) would pick for these sizes and options
+ * (`opts` may be NULL), without launching anything and without a GPU.
+ * `aligned16`: both matrices are 16-byte aligned.  The shape is how Section
+ * 4.5's "thread management" maps onto wave64: lanes_per_row x edge_slots lanes
+ * form a row's thread group, rows_per_wave such groups share a wavefront.
+ * N must be >= 1.
  */
 typedef struct {
     int32_t vector_width;        /* floats per load: 4 (128-bit) or 1              */
@@ -219,7 +266,8 @@ typedef struct {
 } es_launch_info_t;
 
 int es_spmm_launch_info(int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W,
-                        int32_t mode, int32_t aligned16, int32_t backward, es_launch_info_t* info);
+                        int32_t mode, int32_t aligned16, int32_t backward,
+                        const es_launch_opts_t* opts, es_launch_info_t* info);
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* es_spmm_status_string(int status);
@@ -232,42 +280,6 @@ int32_t es_spmm_max_W(int32_t F);
  * `rows_per_wave` rows share a wavefront (Section 4.2's shared-memory width);
  * rows_per_wave = 0 reports the single-row tile.  0 for an invalid argument. */
 int32_t es_spmm_tile_slots(int32_t rows_per_wave);
-
-/*
- * Launch-shape override for es_spmm: how many rows share one wavefront
- * (Section 4.2 assigns a thread group per row; here the group size is
- * 64 / rows_per_wave lanes).  0 restores the built-in choice; otherwise a power
- * of two in [1, 64], lowered when F needs more lanes per row.  Process-wide
- * (an atomic setting: a call racing with the setter sees the old or the new
- * value); meant for tuning sweeps and tests.  Every value yields the
- * same sampled edges; Y differs only by fp32 summation order.
- */
-int es_spmm_set_rows_per_wave(int32_t rows_per_wave);
-
-/*
- * Column-slicing override for es_spmm / es_spmm_norm: cap the lanes that span
- * the feature columns at `lanes` (4, 8, 16, 32 or 64; 0 restores the built-in
- * choice), so that one workgroup covers only 4 * lanes columns and the launch
- * sweeps all rows once per column slice.  With lanes = 8 a gathered piece of an
- * X row is exactly one 128-byte line, and for graphs whose column ids are
- * clustered (community-ordered graphs) the X rows one XCD needs at a time then
- * fit its L2.  The sampler is evaluated once per slice, so graphs without such
- * locality only pay for it.  Same sampled edges for every value; process-wide
- * atomic setting.
- */
-int es_spmm_set_lanes_per_row(int32_t lanes);
-
-/*
- * Long-row threshold override.  A row keeping more than `entries` sampled
- * entries is not summed by one wavefront but cut into 256-entry segments that
- * several workgroups process in parallel (load balance for the skewed degree
- * distributions Section 4.5 "load balancing" describes; sampled rows never
- * exceed W, so this matters for ES_FULL and for very large W).  0 restores the
- * built-in choice (derived from nnz, F and the launch shape); any positive
- * value is legal.
- * Process-wide atomic setting; for tuning sweeps and tests.
- */
-int es_spmm_set_long_row_threshold(int32_t entries);
 
 #ifdef __cplusplus
 }

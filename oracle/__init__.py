@@ -38,7 +38,9 @@ def _load():
     global _lib
     if _lib is not None:
         return _lib
-    lib = ctypes.CDLL(build())
+    # ES_ORACLE_LIBRARY: a build of es_oracle.c made elsewhere (the sanitizer
+    # test points the pin suite at an ASan/UBSan-instrumented one)
+    lib = ctypes.CDLL(os.environ.get("ES_ORACLE_LIBRARY") or build())
     i32p = ctypes.POINTER(ctypes.c_int32)
     i64p = ctypes.POINTER(ctypes.c_int64)
     f32p = ctypes.POINTER(ctypes.c_float)

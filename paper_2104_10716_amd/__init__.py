@@ -13,15 +13,15 @@ from .binding import (  # noqa: F401
     EsSpmmError,
     es_spmm,
     es_spmm_backward,
+    es_spmm_backward_ex,
+    es_spmm_ex,
+    es_launch_opts_t,
     es_spmm_launch_info,
     es_spmm_materialize,
     es_spmm_materialize_transposed,
     es_spmm_max_W,
     es_spmm_norm,
     es_spmm_sample_edges,
-    es_spmm_set_lanes_per_row,
-    es_spmm_set_long_row_threshold,
-    es_spmm_set_rows_per_wave,
     es_spmm_status_string,
     es_spmm_tile_slots,
     es_spmm_validate_csr,

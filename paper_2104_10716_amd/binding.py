@@ -13,6 +13,10 @@ NORMS = {"none": ES_NORM_NONE, "mean": ES_NORM_MEAN, "rsqrt": ES_NORM_RSQRT, "re
          "inv_degree": ES_NORM_INV_DEGREE}
 
 
+class es_launch_opts_t(ctypes.Structure):
+    _fields_ = [("rows_per_wave", ctypes.c_int32), ("lanes_per_row", ctypes.c_int32),
+                ("long_row_threshold", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
 
 class es_launch_info_t(ctypes.Structure):
     _fields_ = [("vector_width", ctypes.c_int32), ("aligned", ctypes.c_int32),
@@ -24,7 +28,8 @@ class es_launch_info_t(ctypes.Structure):
 
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libes_spmm.so")
+# ES_SPMM_LIBRARY: load another build of the same sources (an instrumented one, say)
+_LIB_PATH = os.environ.get("ES_SPMM_LIBRARY") or os.path.join(_PKG, "libes_spmm.so")
 _lib = None
 
 
@@ -60,6 +65,11 @@ def load_library():
                                  ctypes.c_uint64, ctypes.c_int32, vp]
     lib.es_spmm_backward.restype = ctypes.c_int
     lib.es_spmm_backward.argtypes = lib.es_spmm_norm.argtypes
+    optp = ctypes.POINTER(es_launch_opts_t)
+    lib.es_spmm_ex.restype = ctypes.c_int
+    lib.es_spmm_ex.argtypes = lib.es_spmm_norm.argtypes[:-1] + [optp, vp]
+    lib.es_spmm_backward_ex.restype = ctypes.c_int
+    lib.es_spmm_backward_ex.argtypes = lib.es_spmm_ex.argtypes
     lib.es_spmm_sample_edges.restype = ctypes.c_int
     lib.es_spmm_sample_edges.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                          ctypes.c_uint64, ctypes.c_int32, vp, vp, vp]
@@ -75,19 +85,13 @@ def load_library():
     lib.es_spmm_launch_info.restype = ctypes.c_int
     lib.es_spmm_launch_info.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                         ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
-                                        ctypes.c_int32, ctypes.POINTER(es_launch_info_t)]
+                                        ctypes.c_int32, optp, ctypes.POINTER(es_launch_info_t)]
     lib.es_spmm_status_string.restype = ctypes.c_char_p
     lib.es_spmm_status_string.argtypes = [ctypes.c_int]
     lib.es_spmm_max_W.restype = ctypes.c_int32
     lib.es_spmm_max_W.argtypes = [ctypes.c_int32]
     lib.es_spmm_tile_slots.restype = ctypes.c_int32
     lib.es_spmm_tile_slots.argtypes = [ctypes.c_int32]
-    lib.es_spmm_set_rows_per_wave.restype = ctypes.c_int
-    lib.es_spmm_set_rows_per_wave.argtypes = [ctypes.c_int32]
-    lib.es_spmm_set_lanes_per_row.restype = ctypes.c_int
-    lib.es_spmm_set_lanes_per_row.argtypes = [ctypes.c_int32]
-    lib.es_spmm_set_long_row_threshold.restype = ctypes.c_int
-    lib.es_spmm_set_long_row_threshold.argtypes = [ctypes.c_int32]
     _lib = lib
     return lib
 
@@ -127,22 +131,16 @@ def es_spmm_tile_slots(rows_per_wave: int = 0) -> int:
     return int(load_library().es_spmm_tile_slots(int(rows_per_wave)))
 
 
-def es_spmm_set_rows_per_wave(rows_per_wave: int) -> None:
-    rc = load_library().es_spmm_set_rows_per_wave(int(rows_per_wave))
-    if rc != 0:
-        raise EsSpmmError(rc, "es_spmm_set_rows_per_wave")
-
-
-def es_spmm_set_lanes_per_row(lanes: int) -> None:
-    rc = load_library().es_spmm_set_lanes_per_row(int(lanes))
-    if rc != 0:
-        raise EsSpmmError(rc, "es_spmm_set_lanes_per_row")
-
-
-def es_spmm_set_long_row_threshold(entries: int) -> None:
-    rc = load_library().es_spmm_set_long_row_threshold(int(entries))
-    if rc != 0:
-        raise EsSpmmError(rc, "es_spmm_set_long_row_threshold")
+def _opts_ptr(opts):
+    """None, an es_launch_opts_t, or a dict with its field names -> ctypes pointer (or None)."""
+    if opts is None:
+        return None
+    if isinstance(opts, dict):
+        unknown = set(opts) - {name for name, _ in es_launch_opts_t._fields_}
+        if unknown:
+            raise ValueError(f"unknown launch option(s): {sorted(unknown)}")
+        opts = es_launch_opts_t(**{k: int(v) for k, v in opts.items()})
+    return ctypes.byref(opts)
 
 
 def _spmm_args(rowptr, colidx, vals, X, Y, F, nnz):
@@ -193,6 +191,32 @@ def es_spmm_norm(rowptr, colidx, vals, X, Y, W: int, mode, seed: int = 0, norm="
     if rc != 0:
         raise EsSpmmError(rc, "es_spmm_norm")
     return Y
+
+
+def es_spmm_ex(rowptr, colidx, vals, X, Y, W: int, mode, seed: int = 0, norm="none", opts=None,
+               F: Optional[int] = None, stream=None, nnz: Optional[int] = None):
+    """es_spmm_norm with per-call launch options (None, a dict of es_launch_opts_t fields, or the struct)."""
+    lib = load_library()
+    args = _spmm_args(rowptr, colidx, vals, X, Y, F, nnz)
+    nm = NORMS[norm] if isinstance(norm, str) else int(norm)
+    rc = lib.es_spmm_ex(*args, int(W), _mode(mode), int(seed) & 0xFFFFFFFFFFFFFFFF, nm, _opts_ptr(opts),
+                        _stream_ptr(stream))
+    if rc != 0:
+        raise EsSpmmError(rc, "es_spmm_ex")
+    return Y
+
+
+def es_spmm_backward_ex(rowptr, colidx, vals, dY, dX, W: int, mode, seed: int = 0, norm="none", opts=None,
+                        F: Optional[int] = None, stream=None, nnz: Optional[int] = None):
+    """es_spmm_backward with per-call launch options."""
+    lib = load_library()
+    args = _spmm_args(rowptr, colidx, vals, dY, dX, F, nnz)
+    nm = NORMS[norm] if isinstance(norm, str) else int(norm)
+    rc = lib.es_spmm_backward_ex(*args, int(W), _mode(mode), int(seed) & 0xFFFFFFFFFFFFFFFF, nm,
+                                 _opts_ptr(opts), _stream_ptr(stream))
+    if rc != 0:
+        raise EsSpmmError(rc, "es_spmm_backward_ex")
+    return dX
 
 
 def es_spmm_backward(rowptr, colidx, vals, dY, dX, W: int, mode, seed: int = 0, norm="none",
@@ -261,12 +285,14 @@ def es_spmm_materialize(rowptr, colidx, vals, W: int, mode, seed: int = 0, out_r
 
 
 def es_spmm_launch_info(N: int, nnz: int, F: int, W: int, mode, ldx: Optional[int] = None,
-                        ldy: Optional[int] = None, aligned16: bool = True, backward: bool = False) -> dict:
+                        ldy: Optional[int] = None, aligned16: bool = True, backward: bool = False,
+                        opts=None) -> dict:
     """Launch shape the library would pick (host-only; needs no GPU)."""
     info = es_launch_info_t()
     rc = load_library().es_spmm_launch_info(int(N), int(nnz), int(F), int(F if ldx is None else ldx),
                                             int(F if ldy is None else ldy), int(W), _mode(mode),
-                                            int(bool(aligned16)), int(bool(backward)), ctypes.byref(info))
+                                            int(bool(aligned16)), int(bool(backward)), _opts_ptr(opts),
+                                            ctypes.byref(info))
     if rc != 0:
         raise EsSpmmError(rc, "es_spmm_launch_info")
     return {name: int(getattr(info, name)) for name, _ in es_launch_info_t._fields_}

@@ -20,9 +20,11 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, out: str = LIB, extra_flags=()) -> str:
+    """Compile the library to `out` (default: in-tree).  `extra_flags` are added
+    to the hipcc line (host-side instrumentation for the sanitizer test)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + [SRC, "-o", LIB]
+    cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + [SRC, "-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -32,7 +34,7 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + res.stderr)
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

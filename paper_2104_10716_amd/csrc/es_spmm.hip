@@ -30,8 +30,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include <atomic>
-
 #include "es_spmm.h"
 
 #include "es_common.h"
@@ -134,11 +132,33 @@ int32_t pick_long_k(const Shape& s, int logR, double entries, int F)
     return v < kLongMin ? kLongMin : v;
 }
 
-// Process-wide overrides (relaxed atomics: a call racing with a setter sees
-// either the old or the new value, never a torn one).
-std::atomic<int32_t> g_force_logR{-1};   // es_spmm_set_rows_per_wave; -1 = heuristic
-std::atomic<int32_t> g_force_long_k{0};  // es_spmm_set_long_row_threshold; 0 = heuristic
-std::atomic<int32_t> g_force_G{0};       // es_spmm_set_lanes_per_row; 0 = heuristic
+// Per-call overrides, parsed from an es_launch_opts_t (absent = the heuristic).
+struct Overrides {
+    int logR = -1;             // rows_per_wave as a power of two, -1 = heuristic
+    int G = 0;                 // lanes_per_row cap, 0 = heuristic, -1 = never slice
+    int32_t long_k = 0;        // long-row threshold, 0 = heuristic
+};
+
+int parse_opts(const es_launch_opts_t* opts, Overrides* ov)
+{
+    *ov = Overrides();
+    if (!opts) return ES_OK;
+    if (opts->reserved != 0) return ES_ERR_INVALID_ARG;
+    const int32_t rpw = opts->rows_per_wave;
+    if (rpw != 0) {
+        if (rpw < 1 || rpw > 64 || (rpw & (rpw - 1))) return ES_ERR_INVALID_ARG;
+        int lg = 0;
+        while ((1 << lg) < rpw) ++lg;
+        ov->logR = lg;
+    }
+    const int32_t lanes = opts->lanes_per_row;
+    if (lanes != 0 && lanes != -1 && lanes != 4 && lanes != 8 && lanes != 16 && lanes != 32 && lanes != 64)
+        return ES_ERR_INVALID_ARG;
+    ov->G = lanes;
+    if (opts->long_row_threshold < 0) return ES_ERR_INVALID_ARG;
+    ov->long_k = opts->long_row_threshold;
+    return ES_OK;
+}
 
 // Rows per wave for the kernels that only walk the sampler (materialise,
 // transpose): about one lane per kept entry of a typical row; a whole wave per
@@ -177,7 +197,7 @@ int check_sizes(int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int
 // Launch shape for N >= 1 rows.  `aligned`: F and both row strides are
 // multiples of 4 and both matrices are 16-byte aligned.
 int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool aligned, bool backward,
-              Plan* p)
+              const Overrides& ov, Plan* p)
 {
     Shape s = pick_shape(F, aligned);
     if (backward) {                                        // see launch_backward
@@ -187,7 +207,7 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
         if (s.G > 64) s.G = 64;
         s.CH = F > 128 ? 4 : F > 64 ? 2 : 1;
     }
-    const int32_t force_G = g_force_G.load(std::memory_order_relaxed);
+    const int32_t force_G = ov.G;
     if (!backward && force_G > 0 && s.vec == 4 && force_G < s.G) {
         s.G = force_G;                                     // narrower column blocks, more of them
         s.CH = 1;
@@ -197,7 +217,7 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
     double mean = (double)nnz / (double)N;
     if (mode != ES_FULL && mean > (double)W) mean = (double)W;
     int logR = pick_logR(s, mean);
-    const int32_t force_logR = g_force_logR.load(std::memory_order_relaxed);
+    const int32_t force_logR = ov.logR;
     if (force_logR >= 0) {
         logR = force_logR;
         while ((64 >> logR) < s.G) --logR;                 // at least one edge slot per row
@@ -218,8 +238,7 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
     // the long-row part costs a second small launch and a scan of the row
     // pointers; below one tile per row that is more than the tail it removes
     if (mode != ES_FULL && p->long_k < kTileSlots) p->long_k = kTileSlots;
-    const int32_t force_long_k = g_force_long_k.load(std::memory_order_relaxed);
-    if (force_long_k > 0) p->long_k = force_long_k;
+    if (ov.long_k > 0) p->long_k = ov.long_k;
     const bool may_be_long = mode == ES_FULL || W > p->long_k;
     p->long_blocks = may_be_long ? ((N + kLongScanRows - 1) / kLongScanRows) * kLongSplit : 0;
     p->grid_x = p->per_xcd * kNumXcd + p->long_blocks;
@@ -230,10 +249,13 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
 // Shared host path of es_spmm_norm (X -> Y) and es_spmm_backward (dY -> dX).
 int es_run(const int32_t* rowptr, const int32_t* colidx, const float* vals, const float* X, float* Y,
            int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W, int32_t mode,
-           uint64_t seed, int32_t norm, bool backward, void* stream)
+           uint64_t seed, int32_t norm, bool backward, const es_launch_opts_t* opts, void* stream)
 {
     const int bad = check_sizes(N, nnz, F, ldx, ldy, W, mode, norm);
     if (bad != ES_OK) return bad;
+    Overrides ov;
+    const int bad_opts = parse_opts(opts, &ov);
+    if (bad_opts != ES_OK) return bad_opts;
     if (N == 0) return ES_OK;
     if (!rowptr || !X || !Y) return ES_ERR_INVALID_ARG;
     if (nnz > 0 && !colidx) return ES_ERR_INVALID_ARG;
@@ -243,7 +265,7 @@ int es_run(const int32_t* rowptr, const int32_t* colidx, const float* vals, cons
                          (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
                          (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
     Plan p;
-    const int rc = make_plan(N, nnz, F, W, mode, aligned, backward, &p);
+    const int rc = make_plan(N, nnz, F, W, mode, aligned, backward, ov, &p);
     if (rc != ES_OK) return rc;
     const Shape& s = p.s;
 
@@ -298,32 +320,6 @@ int32_t es_spmm_tile_slots(int32_t rows_per_wave)
     return kTileSlots / rows_per_wave;
 }
 
-int es_spmm_set_rows_per_wave(int32_t rows_per_wave)
-{
-    if (rows_per_wave == 0) { g_force_logR.store(-1, std::memory_order_relaxed); return ES_OK; }
-    if (rows_per_wave < 1 || rows_per_wave > 64 || (rows_per_wave & (rows_per_wave - 1)))
-        return ES_ERR_INVALID_ARG;
-    int lg = 0;
-    while ((1 << lg) < rows_per_wave) ++lg;
-    g_force_logR.store(lg, std::memory_order_relaxed);
-    return ES_OK;
-}
-
-int es_spmm_set_lanes_per_row(int32_t lanes)
-{
-    if (lanes != 0 && lanes != 4 && lanes != 8 && lanes != 16 && lanes != 32 && lanes != 64)
-        return ES_ERR_INVALID_ARG;
-    g_force_G.store(lanes, std::memory_order_relaxed);
-    return ES_OK;
-}
-
-int es_spmm_set_long_row_threshold(int32_t entries)
-{
-    if (entries < 0) return ES_ERR_INVALID_ARG;
-    g_force_long_k.store(entries, std::memory_order_relaxed);
-    return ES_OK;
-}
-
 int es_spmm(const int32_t* rowptr, const int32_t* colidx, const float* vals, const float* X,
             float* Y, int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W,
             int32_t mode, uint64_t seed, void* stream)
@@ -336,26 +332,49 @@ int es_spmm_norm(const int32_t* rowptr, const int32_t* colidx, const float* vals
                  float* Y, int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W,
                  int32_t mode, uint64_t seed, int32_t norm, void* stream)
 {
-    return es_run(rowptr, colidx, vals, X, Y, N, nnz, F, ldx, ldy, W, mode, seed, norm, false, stream);
+    return es_run(rowptr, colidx, vals, X, Y, N, nnz, F, ldx, ldy, W, mode, seed, norm, false, nullptr,
+                  stream);
+}
+
+int es_spmm_ex(const int32_t* rowptr, const int32_t* colidx, const float* vals, const float* X,
+               float* Y, int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W,
+               int32_t mode, uint64_t seed, int32_t norm, const es_launch_opts_t* opts, void* stream)
+{
+    return es_run(rowptr, colidx, vals, X, Y, N, nnz, F, ldx, ldy, W, mode, seed, norm, false, opts,
+                  stream);
 }
 
 int es_spmm_backward(const int32_t* rowptr, const int32_t* colidx, const float* vals,
                      const float* dY, float* dX, int64_t N, int64_t nnz, int32_t F, int32_t ldy,
                      int32_t ldx, int32_t W, int32_t mode, uint64_t seed, int32_t norm, void* stream)
 {
-    return es_run(rowptr, colidx, vals, dY, dX, N, nnz, F, ldy, ldx, W, mode, seed, norm, true, stream);
+    return es_run(rowptr, colidx, vals, dY, dX, N, nnz, F, ldy, ldx, W, mode, seed, norm, true, nullptr,
+                  stream);
+}
+
+int es_spmm_backward_ex(const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                        const float* dY, float* dX, int64_t N, int64_t nnz, int32_t F, int32_t ldy,
+                        int32_t ldx, int32_t W, int32_t mode, uint64_t seed, int32_t norm,
+                        const es_launch_opts_t* opts, void* stream)
+{
+    return es_run(rowptr, colidx, vals, dY, dX, N, nnz, F, ldy, ldx, W, mode, seed, norm, true, opts,
+                  stream);
 }
 
 int es_spmm_launch_info(int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W,
-                        int32_t mode, int32_t aligned16, int32_t backward, es_launch_info_t* info)
+                        int32_t mode, int32_t aligned16, int32_t backward,
+                        const es_launch_opts_t* opts, es_launch_info_t* info)
 {
     if (!info) return ES_ERR_INVALID_ARG;
+    Overrides ov;
+    const int bad_opts = parse_opts(opts, &ov);
+    if (bad_opts != ES_OK) return bad_opts;
     const int bad = check_sizes(N, nnz, F, ldx, ldy, W, mode, ES_NORM_NONE);
     if (bad != ES_OK) return bad;
     if (N == 0) return ES_ERR_INVALID_ARG;
     const bool aligned = aligned16 && (F % 4 == 0) && (ldx % 4 == 0) && (ldy % 4 == 0);
     Plan p;
-    const int rc = make_plan(N, nnz, F, W, mode, aligned, backward != 0, &p);
+    const int rc = make_plan(N, nnz, F, W, mode, aligned, backward != 0, ov, &p);
     if (rc != ES_OK) return rc;
     info->vector_width = p.s.vec;
     info->aligned = p.s.aligned ? 1 : 0;

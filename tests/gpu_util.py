@@ -16,12 +16,17 @@ class DeviceCSR:
         self.N = rowptr.shape[0] - 1
         self.F = X.shape[1] if F is None else F
 
-    def run(self, W, mode, seed=0, ldy=None, norm=None):
+    def run(self, W, mode, seed=0, ldy=None, norm=None, opts=None):
+        """NaN-prefilled Y, then the product; `opts` (a dict of es_launch_opts_t
+        fields) routes the call through es_spmm_ex."""
         import torch
         import paper_2104_10716_amd as es
         ldy = self.F if ldy is None else ldy
         Y = torch.full((self.N, ldy), float("nan"), dtype=torch.float32, device=self.X.device)
-        if norm is None:
+        if opts is not None:
+            es.es_spmm_ex(self.rowptr, self.colidx, self.vals, self.X, Y, W, mode, seed,
+                          "none" if norm is None else norm, opts, F=self.F)
+        elif norm is None:
             es.es_spmm(self.rowptr, self.colidx, self.vals, self.X, Y, W, mode, seed, F=self.F)
         else:
             es.es_spmm_norm(self.rowptr, self.colidx, self.vals, self.X, Y, W, mode, seed, norm, F=self.F)
@@ -52,10 +57,10 @@ def check_Y(Y_gpu, Yref, denom, what, tol=TOL):
     return float(rel.max()) if rel.size else 0.0
 
 
-def check_against_oracle(d, W, mode, seed=0, rows=None, ldy=None, what="", norm=None):
+def check_against_oracle(d, W, mode, seed=0, rows=None, ldy=None, what="", norm=None, opts=None):
     """Run es_spmm on DeviceCSR `d` and compare (all rows, or the listed rows)."""
     import oracle
-    Y = d.run(W, mode, seed, ldy=ldy, norm=norm)
+    Y = d.run(W, mode, seed, ldy=ldy, norm=norm, opts=opts)
     Yh = Y.cpu().numpy()
     if ldy is not None and ldy > d.F:
         assert np.isnan(Yh[:, d.F:]).all(), f"{what}: columns beyond F were written"
@@ -67,6 +72,31 @@ def check_against_oracle(d, W, mode, seed=0, rows=None, ldy=None, what="", norm=
     return check_Y(Yh, Yref, den, what or f"{mode} W={W} seed={seed}")
 
 
+def check_every_element(d, W, mode, seed=0, what="", norm=None, opts=None, block_bytes=192 << 20):
+    """Every element of Y on a graph too large for one fp64 reference: the HIP
+    product once, then the oracle row block by row block (Yref + denom of a
+    block stay below `block_bytes`).  Returns the largest normalised error."""
+    import sys
+    import time
+    import oracle
+    what = what or f"{mode} W={W} seed={seed}"
+    Yh = d.run(W, mode, seed, norm=norm, opts=opts).cpu().numpy()
+    block = max(1024, block_bytes // (16 * d.F))
+    worst = 0.0
+    t0 = t_last = time.perf_counter()
+    for lo in range(0, d.N, block):
+        hi = min(d.N, lo + block)
+        rows = np.arange(lo, hi, dtype=np.int64)
+        Yref, den = oracle.spmm(d.h_rowptr, d.h_colidx, d.h_vals, d.h_X, d.F, W, mode, seed, rows=rows,
+                                norm="none" if norm is None else norm)
+        worst = max(worst, check_Y(Yh[lo:hi, :d.F], Yref, den, f"{what} rows [{lo}, {hi})"))
+        if time.perf_counter() - t_last > 30.0:                # keep a long check audibly alive
+            t_last = time.perf_counter()
+            print(f"  {what}: rows below {hi} of {d.N} checked ({t_last - t0:.0f} s)", flush=True)
+            sys.stdout.flush()
+    return worst
+
+
 def check_edges(d, W, mode, seed=0, rows_per_wave=0, what=""):
     import oracle
     pos, cnt = d.edges(W, mode, seed, rows_per_wave)
@@ -76,14 +106,17 @@ def check_edges(d, W, mode, seed=0, rows_per_wave=0, what=""):
     assert np.array_equal(pos.cpu().numpy(), opos), f"{what}: sampled edge lists differ"
 
 
-def check_backward_against_oracle(d, W, mode, seed=0, norm="none", what=""):
+def check_backward_against_oracle(d, W, mode, seed=0, norm="none", what="", opts=None):
     """es_spmm_backward on DeviceCSR `d` (its X plays the upstream gradient dY)
     against the oracle's transposed product, every element."""
     import torch
     import oracle
     import paper_2104_10716_amd as es
     dX = torch.full((d.N, d.F), float("nan"), dtype=torch.float32, device=d.X.device)
-    es.es_spmm_backward(d.rowptr, d.colidx, d.vals, d.X, dX, W, mode, seed, norm, F=d.F)
+    if opts is None:
+        es.es_spmm_backward(d.rowptr, d.colidx, d.vals, d.X, dX, W, mode, seed, norm, F=d.F)
+    else:
+        es.es_spmm_backward_ex(d.rowptr, d.colidx, d.vals, d.X, dX, W, mode, seed, norm, opts, F=d.F)
     torch.cuda.synchronize()
     ref, den = oracle.spmm_backward(d.h_rowptr, d.h_colidx, d.h_vals, d.h_X, d.F, W, mode, seed, norm=norm)
     return check_Y(dX.cpu().numpy(), ref, den, what or f"backward {mode} W={W} seed={seed} norm={norm}")

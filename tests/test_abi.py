@@ -90,5 +90,25 @@ def test_argument_checks_answer_on_the_host(lib):
     assert se(fake, 8, 4, 1, 0, 0, None, fake, None) == -1
     assert se(fake, 2 ** 30, 4, 1, 0, 0, fake, fake, None) == -2  # N*W >= 2^31
     assert se(fake, 0, 4, 1, 0, 0, fake, fake, None) == 0
-    assert lib.es_spmm_set_rows_per_wave(3) == -1
-    assert lib.es_spmm_set_rows_per_wave(0) == 0
+    # per-call launch options are validated on the host too
+    import paper_2104_10716_amd as es
+
+    def call_ex(entry, **opt):
+        o = es.es_launch_opts_t(**opt)
+        return entry(fake, fake, None, fake, fake, 8, 16, 4, 4, 4, 2, 1, 0, 0, ctypes.byref(o), None)
+
+    for entry in (lib.es_spmm_ex, lib.es_spmm_backward_ex):
+        assert call_ex(entry, rows_per_wave=3) == -1
+        assert call_ex(entry, rows_per_wave=128) == -1
+        assert call_ex(entry, lanes_per_row=12) == -1
+        assert call_ex(entry, lanes_per_row=-2) == -1
+        assert call_ex(entry, long_row_threshold=-1) == -1
+        assert call_ex(entry, reserved=5) == -1
+        assert entry(fake, fake, None, fake, fake, 0, 0, 4, 4, 4, 2, 1, 0, 0, None, None) == 0   # N == 0
+
+
+def test_no_process_wide_settings_are_exported(lib):
+    """The ABI is stateless: launch overrides travel with the call."""
+    for name in ("es_spmm_set_rows_per_wave", "es_spmm_set_lanes_per_row", "es_spmm_set_long_row_threshold"):
+        assert not hasattr(lib, name), name
+    assert not [n for n in _declared_functions() if "_set_" in n]

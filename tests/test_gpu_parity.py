@@ -21,10 +21,7 @@ def es():
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     import paper_2104_10716_amd as es
     es.load_library()          # raises if the HIP library is missing: no fallback
-    yield es
-    es.es_spmm_set_rows_per_wave(0)
-    es.es_spmm_set_long_row_threshold(0)
-    es.es_spmm_set_lanes_per_row(0)
+    return es
 
 
 @functools.lru_cache(maxsize=2)
@@ -57,21 +54,20 @@ def test_small_graph_all_modes(es, F, ldx):
     maxdeg = int(np.diff(rowptr).max())
     _say(f"small graph F={F} ldx={ldx} maxdeg={maxdeg}")
     for rpw in (0, 1, 4, 64):
-        es.es_spmm_set_rows_per_wave(rpw)
-        check_against_oracle(d, 0, "full", what=f"full F={F} rpw={rpw}")
+        opts = dict(rows_per_wave=rpw) if rpw else None      # None: the plain es_spmm entry point
+        check_against_oracle(d, 0, "full", what=f"full F={F} rpw={rpw}", opts=opts)
         for mode in ("bucket", "fastrand"):
             for W in (1, 3, 8, maxdeg, maxdeg + 5):
                 for seed in (0, 12345):
                     check_against_oracle(d, W, mode, seed, ldy=ldx + 4 if F % 4 == 0 else None,
-                                         what=f"{mode} F={F} W={W} seed={seed} rpw={rpw}")
-    es.es_spmm_set_rows_per_wave(0)
+                                         what=f"{mode} F={F} W={W} seed={seed} rpw={rpw}", opts=opts)
     # force the long-row path (segments + atomic adds) onto ordinary rows
     for thr in (1, 7):
-        es.es_spmm_set_long_row_threshold(thr)
-        check_against_oracle(d, 0, "full", what=f"full F={F} long-row threshold {thr}")
+        opts = dict(long_row_threshold=thr)
+        check_against_oracle(d, 0, "full", what=f"full F={F} long-row threshold {thr}", opts=opts)
         for mode in ("bucket", "fastrand"):
-            check_against_oracle(d, maxdeg - 1, mode, 12345, what=f"{mode} F={F} long-row threshold {thr}")
-    es.es_spmm_set_long_row_threshold(0)
+            check_against_oracle(d, maxdeg - 1, mode, 12345, what=f"{mode} F={F} long-row threshold {thr}",
+                                 opts=opts)
     for mode in ("bucket", "fastrand"):
         for W in (1, 3, 8, maxdeg):
             for rpw in (0, 1, 2, 8, 64, -1):
@@ -80,25 +76,22 @@ def test_small_graph_all_modes(es, F, ldx):
 
 @pytest.mark.parametrize("F", [64, 100, 256, 520])
 def test_column_slicing_override(es, F):
-    """es_spmm_set_lanes_per_row: narrower column blocks (several per row, the
+    """lanes_per_row option: narrower column blocks (several per row, the
     sampler evaluated once per block) must give the same product."""
     from gpu_util import DeviceCSR, check_against_oracle
     rowptr, colidx, vals, X = _random_graph(900, 14.0, seed=F + 7, F=F, ldx=F + (4 - F % 4) % 4)
     d = DeviceCSR(rowptr, colidx, vals, X, F=F)
-    for lanes in (4, 8, 16, 32, 64, 0):
-        es.es_spmm_set_lanes_per_row(lanes)
+    for lanes in (4, 8, 16, 32, 64, 0, -1):
         for thr in (0, 6):
-            es.es_spmm_set_long_row_threshold(thr)
+            opts = dict(lanes_per_row=lanes, long_row_threshold=thr)
             for mode, W in (("full", 0), ("bucket", 5), ("fastrand", 5), ("fastrand", 25)):
-                check_against_oracle(d, W, mode, 3, norm="mean",
+                check_against_oracle(d, W, mode, 3, norm="mean", opts=opts,
                                      what=f"lanes={lanes} thr={thr} F={F} {mode} W={W}")
-    es.es_spmm_set_long_row_threshold(0)
-    es.es_spmm_set_lanes_per_row(0)
 
 
 def test_randomised_shapes(es):
     """Seeded sweep over random combinations of graph size, degree, F, row
-    strides, W, mode, seed, row factor and the three launch overrides, forward
+    strides, W, mode, seed, row factor and the per-call launch options, forward
     and transposed, each against the oracle."""
     import torch
     from gpu_util import DeviceCSR, check_against_oracle, check_backward_against_oracle, check_edges
@@ -120,20 +113,15 @@ def test_randomised_shapes(es):
         rpw = int(rng.choice([0, 0, 1, 2, 16, 64]))
         thr = int(rng.choice([0, 0, 1, 3, 40]))
         lanes = int(rng.choice([0, 0, 0, 4, 16]))
-        es.es_spmm_set_rows_per_wave(rpw)
-        es.es_spmm_set_long_row_threshold(thr)
-        es.es_spmm_set_lanes_per_row(lanes)
+        opts = dict(rows_per_wave=rpw, long_row_threshold=thr, lanes_per_row=lanes)
         what = (f"case {case}: n={n} avg={avg} F={F} ld={F + pad} {mode} W={W} seed={seed} norm={norm} "
                 f"rpw={rpw} thr={thr} lanes={lanes}")
         _say(what)
         ldy = F + int(rng.choice([0, 0, 2, 4]))
-        check_against_oracle(d, W, mode, seed, ldy=ldy, norm=norm, what=what)
-        check_backward_against_oracle(d, W, mode, seed, norm, what="backward " + what)
+        check_against_oracle(d, W, mode, seed, ldy=ldy, norm=norm, what=what, opts=opts)
+        check_backward_against_oracle(d, W, mode, seed, norm, what="backward " + what, opts=opts)
         if mode != "full":
             check_edges(d, W, mode, seed, int(rng.choice([0, 1, 4, -1])), what="edges " + what)
-    es.es_spmm_set_rows_per_wave(0)
-    es.es_spmm_set_long_row_threshold(0)
-    es.es_spmm_set_lanes_per_row(0)
 
 
 def test_long_rows_span_several_tiles(es):
@@ -156,19 +144,18 @@ def test_long_rows_span_several_tiles(es):
         X = rng.uniform(-1, 1, (n, F)).astype(np.float32)
         d = DeviceCSR(rowptr, colidx, vals, X)
         for rpw in (0, 1, 4, 16):
-            es.es_spmm_set_rows_per_wave(rpw)
+            opts = dict(rows_per_wave=rpw)
             _say(f"long rows F={F} rpw={rpw}")
-            check_against_oracle(d, 0, "full", what=f"long full F={F} rpw={rpw}")
+            check_against_oracle(d, 0, "full", what=f"long full F={F} rpw={rpw}", opts=opts)
             for W in (16, 512, 576, 600, 1153, 3000):
                 for mode in ("bucket", "fastrand"):
-                    check_against_oracle(d, W, mode, 77, what=f"long {mode} F={F} W={W} rpw={rpw}")
-        es.es_spmm_set_rows_per_wave(0)
+                    check_against_oracle(d, W, mode, 77, what=f"long {mode} F={F} W={W} rpw={rpw}", opts=opts)
         for thr in (100, 512, 1000, 5000):  # move the long-row threshold around
-            es.es_spmm_set_long_row_threshold(thr)
-            check_against_oracle(d, 0, "full", what=f"long full F={F} threshold {thr}")
+            opts = dict(long_row_threshold=thr)
+            check_against_oracle(d, 0, "full", what=f"long full F={F} threshold {thr}", opts=opts)
             for W in (600, 1153, 3000):
-                check_against_oracle(d, W, "fastrand", 77, what=f"long fastrand F={F} W={W} threshold {thr}")
-        es.es_spmm_set_long_row_threshold(0)
+                check_against_oracle(d, W, "fastrand", 77, what=f"long fastrand F={F} W={W} threshold {thr}",
+                                     opts=opts)
     for W in (16, 512, 576, 600, 1153, 3000):
         for rpw in (0, 1, 8, -1):
             for seed in (0, 77):
@@ -201,16 +188,16 @@ def test_degenerate_inputs(es):
     import paper_2104_10716_amd as esm
     rowptr, colidx, vals, X = _random_graph(400, 40.0, seed=8, F=32)
     dh = DeviceCSR(rowptr, colidx, vals, X)
-    esm.es_spmm_set_long_row_threshold(16)
-    for mode, W in (("full", 0), ("fastrand", 6), ("fastrand", 30)):
-        ref = dh.run(W, mode, 3)
-        for hint in (0, 1, 10 ** 9):
-            Y = torch.empty_like(ref)
-            esm.es_spmm(dh.rowptr, dh.colidx, dh.vals, dh.X, Y, W, mode, 3, nnz=hint)
-            torch.cuda.synchronize()
-            assert torch.allclose(Y, ref, rtol=1e-4, atol=1e-5), (mode, hint)
-        check_against_oracle(dh, W, mode, 3, what=f"nnz hint {mode}")
-    esm.es_spmm_set_long_row_threshold(0)
+    for thr in (0, 16):
+        opts = dict(long_row_threshold=thr)
+        for mode, W in (("full", 0), ("fastrand", 6), ("fastrand", 30)):
+            ref = dh.run(W, mode, 3, opts=opts)
+            for hint in (0, 1, 10 ** 9):
+                Y = torch.empty_like(ref)
+                esm.es_spmm_ex(dh.rowptr, dh.colidx, dh.vals, dh.X, Y, W, mode, 3, "none", opts, nnz=hint)
+                torch.cuda.synchronize()
+                assert torch.allclose(Y, ref, rtol=1e-4, atol=1e-5), (mode, hint)
+            check_against_oracle(dh, W, mode, 3, what=f"nnz hint {mode}", opts=opts)
     # N == 0 is a no-op
     e = torch.empty((0, 4), dtype=torch.float32, device="cuda:0")
     es.es_spmm(torch.zeros(1, dtype=torch.int32, device="cuda:0"),
@@ -226,6 +213,12 @@ def test_degenerate_inputs(es):
         es.es_spmm_norm(du.rowptr, du.colidx, du.vals, du.X, Yk, 4, "bucket", 0, 99)
     with pytest.raises(es.EsSpmmError):
         es.es_spmm_backward(du.rowptr, du.colidx, du.vals, du.X, Yk, 0, "bucket")
+    for bad_opts in (dict(rows_per_wave=3), dict(rows_per_wave=128), dict(lanes_per_row=12),
+                     dict(long_row_threshold=-1), dict(reserved=1)):
+        with pytest.raises(es.EsSpmmError):
+            es.es_spmm_ex(du.rowptr, du.colidx, du.vals, du.X, Yk, 4, "bucket", 0, "none", bad_opts)
+        with pytest.raises(es.EsSpmmError):
+            es.es_spmm_backward_ex(du.rowptr, du.colidx, du.vals, du.X, Yk, 4, "bucket", 0, "none", bad_opts)
     torch.cuda.synchronize()
     assert bool((Yk == 7.0).all())
     # runs on a non-default stream too
@@ -246,10 +239,10 @@ def test_in_kernel_normalisation(es, norm):
         rowptr, colidx, vals, X = _random_graph(900, 25.0, seed=F, F=F, empty_frac=0.1)
         d = DeviceCSR(rowptr, colidx, vals, X)
         for thr in (0, 9):
-            es.es_spmm_set_long_row_threshold(thr)
+            opts = dict(long_row_threshold=thr) if thr else None     # None: the es_spmm_norm entry point
             for mode, W in (("full", 0), ("bucket", 6), ("fastrand", 6), ("fastrand", 20), ("fastrand", 1000)):
-                check_against_oracle(d, W, mode, 11, norm=norm, what=f"norm={norm} {mode} W={W} F={F} thr={thr}")
-        es.es_spmm_set_long_row_threshold(0)
+                check_against_oracle(d, W, mode, 11, norm=norm, opts=opts,
+                                     what=f"norm={norm} {mode} W={W} F={F} thr={thr}")
     w = _workload(2)
     d = DeviceCSR(w.rowptr, w.colidx, w.vals, w.X)
     for mode, W in (("full", 0), ("fastrand", 16), ("bucket", 64)):
@@ -268,16 +261,13 @@ def test_backward_small_graphs(es, F, ldx):
     d = DeviceCSR(rowptr, colidx, vals, dY, F=F)
     maxdeg = int(np.diff(rowptr).max())
     for rpw in (0, 1, 8):
-        es.es_spmm_set_rows_per_wave(rpw)
         for thr in (0, 5):
-            es.es_spmm_set_long_row_threshold(thr)
+            opts = dict(rows_per_wave=rpw, long_row_threshold=thr) if (rpw or thr) else None
             for mode, W in (("full", 0), ("bucket", 4), ("fastrand", 4), ("fastrand", maxdeg - 1),
                             ("fastrand", maxdeg + 3)):
                 for norm in ("none", "mean", "rescale"):
-                    check_backward_against_oracle(d, W, mode, 31, norm,
+                    check_backward_against_oracle(d, W, mode, 31, norm, opts=opts,
                                                   what=f"backward F={F} {mode} W={W} {norm} rpw={rpw} thr={thr}")
-    es.es_spmm_set_rows_per_wave(0)
-    es.es_spmm_set_long_row_threshold(0)
     du = DeviceCSR(rowptr, colidx, None, dY, F=F)              # unweighted
     check_backward_against_oracle(du, 4, "fastrand", 1, what=f"backward unit values F={F}")
 
@@ -364,20 +354,20 @@ def test_hip_graph_capture_and_replay(es):
     from gpu_util import DeviceCSR, check_against_oracle
     rowptr, colidx, vals, X = _random_graph(3000, 20.0, seed=21, F=64)
     d = DeviceCSR(rowptr, colidx, vals, X)
-    es.es_spmm_set_long_row_threshold(24)          # full mode then uses both kernels
+    long_opts = dict(long_row_threshold=24)        # full mode then uses both kernels
     Yf = torch.zeros((d.N, d.F), dtype=torch.float32, device="cuda:0")
     Ys = torch.zeros_like(Yf)
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
         for _ in range(2):                         # warm-up outside capture
-            es.es_spmm(d.rowptr, d.colidx, d.vals, d.X, Yf, 0, "full")
+            es.es_spmm_ex(d.rowptr, d.colidx, d.vals, d.X, Yf, 0, "full", 0, "none", long_opts)
             es.es_spmm(d.rowptr, d.colidx, d.vals, d.X, Ys, 8, "fastrand", 5)
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
-        es.es_spmm(d.rowptr, d.colidx, d.vals, d.X, Yf, 0, "full")
+        es.es_spmm_ex(d.rowptr, d.colidx, d.vals, d.X, Yf, 0, "full", 0, "none", long_opts)
         es.es_spmm(d.rowptr, d.colidx, d.vals, d.X, Ys, 8, "fastrand", 5)
     for rep in range(4):
         Yf.fill_(float("nan"))
@@ -389,13 +379,12 @@ def test_hip_graph_capture_and_replay(es):
         torch.cuda.synchronize()
         eager_s = d.run(8, "fastrand", 5)
         assert torch.equal(Ys, eager_s), f"replay {rep}: sampled result differs from eager"
-        eager_f = d.run(0, "full")
+        eager_f = d.run(0, "full", opts=long_opts)
         assert torch.allclose(Yf, eager_f, rtol=1e-4, atol=1e-5), f"replay {rep}: full result differs"
         import oracle
         Yref, den = oracle.spmm(rowptr, colidx, vals, d.h_X, d.F, 8, "fastrand", 5)
         from gpu_util import check_Y
         check_Y(Ys.cpu().numpy(), Yref, den, f"graph replay {rep}")
-    es.es_spmm_set_long_row_threshold(0)
 
 
 def test_validate_csr(es):
@@ -443,30 +432,124 @@ def test_validate_csr(es):
 
 
 def test_concurrent_streams(es):
-    """Calls on two streams at once (different graphs, interleaved launches)
-    give what the same calls give one after the other: the library keeps no
-    per-call state and every kernel works only on its arguments."""
+    """Calls on two streams at once (different graphs, interleaved launches,
+    DIFFERENT launch options on each stream) give what the same calls give one
+    after the other: options travel with the call, the library keeps no state
+    and every kernel works only on its arguments."""
     import torch
     from gpu_util import DeviceCSR
     ga = DeviceCSR(*_random_graph(20_000, 30.0, seed=51, F=64))
     gb = DeviceCSR(*_random_graph(15_000, 8.0, seed=52, F=128))
-    cases = [(ga, 16, "fastrand", 4), (gb, 0, "full", 0), (ga, 0, "full", 0), (gb, 5, "bucket", 0),
-             (ga, 100, "fastrand", 9), (gb, 64, "fastrand", 2)]
-    serial = [d.run(W, mode, seed) for d, W, mode, seed in cases]
+    oa = dict(rows_per_wave=1, long_row_threshold=20)            # stream 1: wave per row, long-row path on
+    ob = dict(rows_per_wave=8, lanes_per_row=8)                  # stream 2: 8 rows per wave, 32-column slices
+    cases = [(ga, 16, "fastrand", 4, oa), (gb, 0, "full", 0, ob), (ga, 0, "full", 0, oa), (gb, 5, "bucket", 0, ob),
+             (ga, 100, "fastrand", 9, oa), (gb, 64, "fastrand", 2, ob)]
+    serial = [d.run(W, mode, seed, opts=o) for d, W, mode, seed, o in cases]
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
     outs = [torch.full((d.N, d.F), float("nan"), dtype=torch.float32, device="cuda:0") for d, *_ in cases]
     torch.cuda.synchronize()
     for rep in range(3):
-        for i, (d, W, mode, seed) in enumerate(cases):
+        for i, (d, W, mode, seed, o) in enumerate(cases):
             with torch.cuda.stream(s1 if i % 2 == 0 else s2):
-                es.es_spmm(d.rowptr, d.colidx, d.vals, d.X, outs[i], W, mode, seed)
+                es.es_spmm_ex(d.rowptr, d.colidx, d.vals, d.X, outs[i], W, mode, seed, "none", o)
     s1.synchronize()
     s2.synchronize()
-    for i, (d, W, mode, seed) in enumerate(cases):
-        if mode == "full":
+    for i, (d, W, mode, seed, o) in enumerate(cases):
+        atomic_rows = mode == "full" or (o is oa and W > 20)     # long-row part: summation order is free
+        if atomic_rows:
             assert torch.allclose(outs[i], serial[i], rtol=1e-4, atol=1e-5), i
         else:
             assert torch.equal(outs[i], serial[i]), i
+    # the launch shape each stream asked for is the one its calls got
+    ia = es.es_spmm_launch_info(ga.N, ga.h_colidx.size, 64, 16, "fastrand", opts=oa)
+    ib = es.es_spmm_launch_info(gb.N, gb.h_colidx.size, 128, 5, "bucket", opts=ob)
+    assert ia["rows_per_wave"] == 1 and ia["long_row_threshold"] == 20
+    assert ib["rows_per_wave"] == 8 and ib["lanes_per_row"] == 8 and ib["grid_y"] == 4
+
+
+def _one_row_graph(n):
+    """rowptr of a 3-row matrix whose middle row has n entries (only the row
+    pointers matter to the sampler export)."""
+    return np.array([0, 5, 5 + n, 5 + n + 7], dtype=np.int32)
+
+
+@pytest.mark.parametrize("n,W", [(338_699, 3), (338_699, 64), (200_848_507, 3), (200_848_507, 64),
+                                 (2 * 338_699, 64), (577 * 1000, 700)])
+def test_sampler_multiplier_fallbacks(es, n, W):
+    """Row lengths divisible by 577*587 (multiplier 593) and by 577*587*593
+    (multiplier 599): the device sampler's picks equal the oracle's, seeded and
+    unseeded, on every lane schedule (Equation 2 with the distinctness reading)."""
+    import torch
+    import oracle
+    rowptr = _one_row_graph(n)
+    P = oracle.multiplier(n)
+    assert P == (599 if n % (577 * 587 * 593) == 0 else 593 if n % (577 * 587) == 0 else 587)
+    drp = torch.from_numpy(rowptr).to("cuda:0")
+    for seed in (0, 0xDEADBEEFCAFE):
+        opos, ocnt = oracle.kept(rowptr, W, "fastrand", seed)
+        assert np.unique(opos[1]).size == W
+        for rpw in (0, 1, 4, 64, -1):
+            pos, cnt = es.es_spmm_sample_edges(drp, W, "fastrand", seed, rpw)
+            torch.cuda.synchronize()
+            assert np.array_equal(cnt.cpu().numpy(), ocnt), (n, W, seed, rpw)
+            assert np.array_equal(pos.cpu().numpy(), opos), (n, W, seed, rpw)
+    _say(f"sampler n={n} (multiplier {P}) W={W}: picks identical to the oracle")
+
+
+@pytest.mark.parametrize("n", [200_000, 338_699 * 2, 1_000_003])
+def test_sampler_slots_above_65535(es, n):
+    """W = 70 000 on a row longer than W: slots >= 65 536 take the 64-bit start
+    index in the device sampler (tile refills for rows_per_wave >= 0, segment
+    restarts for the long-row schedule)."""
+    import torch
+    import oracle
+    W = 70_000
+    rowptr = _one_row_graph(n)
+    drp = torch.from_numpy(rowptr).to("cuda:0")
+    for seed in (0, 991):
+        opos, ocnt = oracle.kept(rowptr, W, "fastrand", seed)
+        for rpw in (0, -1, 2):
+            pos, cnt = es.es_spmm_sample_edges(drp, W, "fastrand", seed, rpw)
+            torch.cuda.synchronize()
+            assert np.array_equal(cnt.cpu().numpy(), ocnt), (n, seed, rpw)
+            got = pos.cpu().numpy()
+            assert np.array_equal(got, opos), (n, seed, rpw, int(np.argmax((got != opos).any(axis=0))))
+        opos_b, _ = oracle.kept(rowptr, W, "bucket", seed)
+        pos, _ = es.es_spmm_sample_edges(drp, W, "bucket", seed, -1)
+        assert np.array_equal(pos.cpu().numpy(), opos_b)
+    _say(f"sampler n={n} W={W}: slots up to {W - 1} identical to the oracle")
+
+
+def test_fused_kernel_on_a_very_long_row(es):
+    """One es_spmm call with a row of 400 000 entries and W = 70 000: the fused
+    kernel's own walk (tile refills past slot 65 536 with a wave per row; 256-slot
+    segment restarts on the long-row path) against the oracle, every element."""
+    from gpu_util import DeviceCSR, check_against_oracle
+    rng = np.random.default_rng(17)
+    N = 450_000
+    big = np.sort(rng.choice(N, size=400_000, replace=False)).astype(np.int32)
+    mid = np.sort(rng.choice(N, size=338_699, replace=False)).astype(np.int32)    # multiplier 593
+    small = [np.sort(rng.choice(N, size=L, replace=False)).astype(np.int32) for L in (3, 0, 70_001, 65_537)]
+    lists = [small[0], big, small[1], mid, small[2], small[3]]
+    rowptr = np.zeros(N + 1, dtype=np.int32)
+    lens = np.zeros(N, dtype=np.int64)
+    where = [0, 7, 8, 100, 449_998, 449_999]
+    for r, l in zip(where, lists):
+        lens[r] = l.size
+    rowptr[1:] = np.cumsum(lens)
+    colidx = np.concatenate(lists)
+    vals = rng.standard_normal(colidx.size).astype(np.float32)
+    X = rng.uniform(-1, 1, (N, 8)).astype(np.float32)
+    d = DeviceCSR(rowptr, colidx, vals, X)
+    rows = np.array(where, dtype=np.int64)
+    for W in (70_000, 65_536, 3):
+        for seed in (0, 5):
+            for opts in (dict(rows_per_wave=1, long_row_threshold=2 ** 30), dict(long_row_threshold=1000), None):
+                worst = check_against_oracle(d, W, "fastrand", seed, rows=rows, opts=opts,
+                                             what=f"very long row W={W} seed={seed} opts={opts}")
+    Y = d.run(70_000, "fastrand", 5).cpu().numpy()
+    assert np.isfinite(Y).all() and (Y[1:7] == 0).all()          # the empty rows in between are written
+    _say(f"fused kernel, row of 400 000 entries at W=70 000: within the bound (worst {worst:.2e})")
 
 
 def test_determinism_across_launches(es):
@@ -584,46 +667,57 @@ def test_config2_citation_like_full_size(es):
             _say(f"cfg2 {mode} W={W}: max normalised error {worst:.2e}")
 
 
-def _sample_rows(w, count, seed):
-    """Random rows plus the longest, the shortest and the last row."""
-    deg = np.diff(w.rowptr)
-    rng = np.random.default_rng(seed)
-    rows = set(rng.integers(0, w.N, size=count).tolist())
-    rows.update(np.argsort(deg)[-8:].tolist())
-    rows.update(np.argsort(deg)[:4].tolist())
-    rows.update([0, w.N - 1])
-    return np.array(sorted(rows), dtype=np.int64)
-
-
-def test_config3_social_like_full_size(es):
-    """114 M entries: Y is checked on sampled rows (oracle row by row); edge
-    lists are checked for every row."""
-    from gpu_util import DeviceCSR, check_against_oracle, check_edges
+def _cfg3_device():
+    from gpu_util import DeviceCSR
     w = _workload(3)
-    d = DeviceCSR(w.rowptr, w.colidx, w.vals, w.X)
-    rows = _sample_rows(w, 1500, 3)
-    worst = check_against_oracle(d, 0, "full", rows=rows, what="cfg3 full")
-    _say(f"cfg3 full: max normalised error {worst:.2e} on {rows.size} rows")
+    return w, DeviceCSR(w.rowptr, w.colidx, w.vals, w.X)
+
+
+def test_config3_social_like_full_product(es):
+    """Config 3 (113 M entries, rows up to 20 k): EVERY element of the exact
+    product against the oracle, in row blocks."""
+    from gpu_util import check_every_element
+    w, d = _cfg3_device()
+    worst = check_every_element(d, 0, "full", what="cfg3 full")
+    _say(f"cfg3 full: max normalised error {worst:.2e} over all {w.N} x {w.F} elements")
+
+
+@pytest.mark.parametrize("mode", ["bucket", "fastrand"])
+def test_config3_social_like_every_width(es, mode):
+    """Config 3, every W of the sweep: every element of Y against the oracle."""
+    from gpu_util import check_every_element
+    w, d = _cfg3_device()
     for W in w.Ws:
-        for mode in ("bucket", "fastrand"):
-            worst = check_against_oracle(d, W, mode, 0, rows=rows, what=f"cfg3 {mode} W={W}")
-            _say(f"cfg3 {mode} W={W}: max normalised error {worst:.2e}")
+        worst = check_every_element(d, W, mode, 0, what=f"cfg3 {mode} W={W}")
+        _say(f"cfg3 {mode} W={W}: max normalised error {worst:.2e} over all {w.N} x {w.F} elements")
+
+
+def test_config3_social_like_edge_lists(es):
+    """Config 3: sampled edge lists of every row, bit-exact (smallest and
+    largest W, a 60-bit seed, the long-row sampler schedule)."""
+    from gpu_util import check_edges, check_every_element
+    w, d = _cfg3_device()
     for W in (16, 256):
         for mode in ("bucket", "fastrand"):
             check_edges(d, W, mode, 0)
             _say(f"cfg3 {mode} W={W}: edge lists identical")
-    # seeded rotation, and the long-row sampler schedule, on every row
     check_edges(d, 64, "fastrand", 0xC0FFEE123456789)
     check_edges(d, 64, "fastrand", 3, rows_per_wave=-1)
     check_edges(d, 300, "fastrand", 3, rows_per_wave=-1)
-    worst = check_against_oracle(d, 64, "fastrand", 0xC0FFEE123456789, rows=rows, what="cfg3 fastrand W=64 seeded")
+    worst = check_every_element(d, 64, "fastrand", 0xC0FFEE123456789, what="cfg3 fastrand W=64 seeded")
     _say(f"cfg3 fastrand W=64 with a 60-bit seed: edge lists identical, max normalised error {worst:.2e}")
-    # the widths the paper needs for Bucket on its densest graph (S = 1792, 2304):
-    # several LDS tiles per row, and rows above the long-row threshold
-    for W in (1792, 2304):
-        for mode in ("bucket", "fastrand"):
-            worst = check_against_oracle(d, W, mode, 0, rows=rows, what=f"cfg3 {mode} W={W}")
-            _say(f"cfg3 {mode} W={W}: max normalised error {worst:.2e}")
+
+
+@pytest.mark.parametrize("W", [1792, 2304])
+def test_config3_widths_of_the_paper_densest_graph(es, W):
+    """The widths the paper needs for Bucket on its densest graph (S = 1792,
+    2304): several LDS tiles per row and rows above the long-row threshold;
+    every element against the oracle."""
+    from gpu_util import check_every_element
+    w, d = _cfg3_device()
+    for mode in ("bucket", "fastrand"):
+        worst = check_every_element(d, W, mode, 0, what=f"cfg3 {mode} W={W}")
+        _say(f"cfg3 {mode} W={W}: max normalised error {worst:.2e} over all {w.N} x {w.F} elements")
 
 
 @pytest.mark.parametrize("cfg", [3, 4])
@@ -721,43 +815,69 @@ def test_maximum_sizes_int32_index_range(es):
     torch.cuda.empty_cache()
 
 
-def test_config5_feature_sweep_on_config3_graph(es):
-    """F = 256 and F = 41 stages of the 2-layer GCN forward (layer equation of
-    Section 2.1: GEMM first, then SpMM).  Dense products are formed on the host
-    from seeded inputs and the oracle's own first-stage output, so no oracle
-    input comes from the HIP path."""
-    import oracle
-    from gpu_util import DeviceCSR, check_against_oracle
+def _gcn_first_stage_input():
     from workloads import gcn_operands
     g = _workload(3)
     X0, W1, W2 = gcn_operands(g.N)
     Z1 = (X0 @ W1).astype(np.float32)                           # [N x 256]
-    del X0
-    rows = _sample_rows(g, 600, 5)
+    return g, Z1, W2
+
+
+def test_config5_first_stage_F256(es):
+    """F = 256 stage of the 2-layer GCN forward (layer equation of Section 2.1:
+    GEMM first, then SpMM) on the config-3 graph: every element of Y against
+    the oracle for W = 64 (both strategies) and the exact product."""
+    from gpu_util import DeviceCSR, check_every_element
+    g, Z1, _ = _gcn_first_stage_input()
     d = DeviceCSR(g.rowptr, g.colidx, g.vals, Z1)
     for mode, W in (("bucket", 64), ("fastrand", 64), ("full", 0)):
-        worst = check_against_oracle(d, W, mode, 0, rows=rows, what=f"cfg5 F=256 {mode}")
-        _say(f"cfg5 F=256 {mode} W={W}: max normalised error {worst:.2e}")
-    del d
+        worst = check_every_element(d, W, mode, 0, what=f"cfg5 F=256 {mode}")
+        _say(f"cfg5 F=256 {mode} W={W}: max normalised error {worst:.2e} over all {g.N} x 256 elements")
+
+
+def test_config5_second_stage_F41(es):
+    """F = 41 stage (row stride 41).  The dense products are formed on the host
+    from seeded inputs and the ORACLE's first-stage output, so no oracle input
+    comes from the HIP path.  Every element against the oracle."""
+    import oracle
+    from gpu_util import DeviceCSR, check_every_element
+    g, Z1, W2 = _gcn_first_stage_input()
     H1, _ = oracle.spmm(g.rowptr, g.colidx, g.vals, Z1, 256, 64, "fastrand", 0, want_denom=False)
     Z2 = (np.maximum(H1, 0.0).astype(np.float32) @ W2).astype(np.float32)   # [N x 41]
+    del H1, Z1
     d = DeviceCSR(g.rowptr, g.colidx, g.vals, Z2)
     for mode, W in (("bucket", 64), ("fastrand", 64), ("full", 0)):
-        worst = check_against_oracle(d, W, mode, 0, rows=rows, what=f"cfg5 F=41 {mode}")
-        _say(f"cfg5 F=41 {mode} W={W}: max normalised error {worst:.2e}")
+        worst = check_every_element(d, W, mode, 0, what=f"cfg5 F=41 {mode}")
+        _say(f"cfg5 F=41 {mode} W={W}: max normalised error {worst:.2e} over all {g.N} x 41 elements")
 
 
-def test_config4_copurchase_like_full_size(es):
-    from gpu_util import DeviceCSR, check_against_oracle, check_edges
+def _cfg4_device():
+    from gpu_util import DeviceCSR
     w = _workload(4)
-    d = DeviceCSR(w.rowptr, w.colidx, w.vals, w.X)
-    rows = _sample_rows(w, 3000, 4)
-    worst = check_against_oracle(d, 0, "full", rows=rows, what="cfg4 full")
-    _say(f"cfg4 full: max normalised error {worst:.2e} on {rows.size} rows")
+    return w, DeviceCSR(w.rowptr, w.colidx, w.vals, w.X)
+
+
+def test_config4_copurchase_like_full_product(es):
+    """Config 4 (N = 2.45 M, 120 M entries, F = 128): every element of the
+    exact product against the oracle, in row blocks."""
+    from gpu_util import check_every_element
+    w, d = _cfg4_device()
+    worst = check_every_element(d, 0, "full", what="cfg4 full")
+    _say(f"cfg4 full: max normalised error {worst:.2e} over all {w.N} x {w.F} elements")
+
+
+@pytest.mark.parametrize("mode", ["bucket", "fastrand"])
+def test_config4_copurchase_like_every_width(es, mode):
+    from gpu_util import check_every_element
+    w, d = _cfg4_device()
     for W in w.Ws:
-        for mode in ("bucket", "fastrand"):
-            worst = check_against_oracle(d, W, mode, 0, rows=rows, what=f"cfg4 {mode} W={W}")
-            _say(f"cfg4 {mode} W={W}: max normalised error {worst:.2e}")
+        worst = check_every_element(d, W, mode, 0, what=f"cfg4 {mode} W={W}")
+        _say(f"cfg4 {mode} W={W}: max normalised error {worst:.2e} over all {w.N} x {w.F} elements")
+
+
+def test_config4_copurchase_like_edge_lists(es):
+    from gpu_util import check_edges
+    w, d = _cfg4_device()
     check_edges(d, 32, "fastrand", 0)
     _say("cfg4 fastrand W=32: edge lists identical")
     check_edges(d, 128, "fastrand", 77)

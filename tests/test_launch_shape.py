@@ -7,17 +7,6 @@ import pytest
 import paper_2104_10716_amd as es
 
 
-@pytest.fixture(autouse=True)
-def _reset_overrides():
-    es.es_spmm_set_rows_per_wave(0)
-    es.es_spmm_set_long_row_threshold(0)
-    es.es_spmm_set_lanes_per_row(0)
-    yield
-    es.es_spmm_set_rows_per_wave(0)
-    es.es_spmm_set_long_row_threshold(0)
-    es.es_spmm_set_lanes_per_row(0)
-
-
 SHAPES = [(1, 0), (7, 20), (2708, 13518), (170_000, 2_370_240), (233_000, 113_134_823),
           (2_450_000, 119_569_270)]
 WIDTHS = [1, 2, 3, 4, 5, 16, 17, 41, 48, 64, 100, 128, 130, 256, 512, 602, 1024, 1028, 5000]
@@ -68,34 +57,49 @@ def test_long_rows_are_only_possible_when_the_long_part_is_launched():
         assert (big["long_row_workgroups"] > 0) == (2304 > big["long_row_threshold"])
 
 
-def test_overrides_are_honoured_and_clamped():
-    es.es_spmm_set_rows_per_wave(64)
-    info = es.es_spmm_launch_info(1000, 5000, 64, 8, "bucket")
+def test_options_are_honoured_and_clamped():
+    base = es.es_spmm_launch_info(1000, 5000, 64, 8, "bucket")
+    info = es.es_spmm_launch_info(1000, 5000, 64, 8, "bucket", opts=dict(rows_per_wave=64))
     assert info["lanes_per_row"] == 16 and info["rows_per_wave"] == 4      # lowered to fit G
-    es.es_spmm_set_rows_per_wave(1)
-    assert es.es_spmm_launch_info(1000, 5000, 64, 8, "bucket")["rows_per_wave"] == 1
-    es.es_spmm_set_rows_per_wave(0)
-    es.es_spmm_set_long_row_threshold(7)
-    info = es.es_spmm_launch_info(1000, 5000, 64, 8, "bucket")
+    assert es.es_spmm_launch_info(1000, 5000, 64, 8, "bucket", opts=dict(rows_per_wave=1))["rows_per_wave"] == 1
+    info = es.es_spmm_launch_info(1000, 5000, 64, 8, "bucket", opts=dict(long_row_threshold=7))
     assert info["long_row_threshold"] == 7 and info["long_row_workgroups"] > 0
-    es.es_spmm_set_long_row_threshold(0)
-    assert es.es_spmm_launch_info(1000, 5000, 64, 8, "bucket")["long_row_workgroups"] == 0
+    # options travel with the call: the next call without them sees the heuristic again
+    assert es.es_spmm_launch_info(1000, 5000, 64, 8, "bucket") == base
+    assert base["long_row_workgroups"] == 0
+    # an all-zero struct is the same as no struct
+    assert es.es_spmm_launch_info(1000, 5000, 64, 8, "bucket", opts={}) == base
+    for bad in (dict(rows_per_wave=3), dict(rows_per_wave=-1), dict(lanes_per_row=12), dict(lanes_per_row=-2),
+                dict(long_row_threshold=-4), dict(reserved=1)):
+        with pytest.raises(es.EsSpmmError):
+            es.es_spmm_launch_info(1000, 5000, 64, 8, "bucket", opts=bad)
 
 
-def test_column_slicing_override_only_narrows():
-    base = es.es_spmm_launch_info(1000, 9000, 128, 8, "bucket")
+def test_option_grid_keeps_the_shape_invariants():
+    for (N, nnz), F, mode in itertools.product(SHAPES[1:], (3, 16, 41, 64, 128, 256, 602), ("full", "fastrand")):
+        for rpw, lanes, thr in itertools.product((0, 1, 8, 64), (0, -1, 4, 8, 32, 64), (0, 1, 100)):
+            opts = dict(rows_per_wave=rpw, lanes_per_row=lanes, long_row_threshold=thr)
+            for backward in (False, True):
+                info = es.es_spmm_launch_info(N, nnz, F, 64, mode, backward=backward, opts=opts)
+                assert info["long_row_threshold"] >= (thr if thr else 64)
+                if thr:
+                    assert info["long_row_threshold"] == thr
+                G, CH, V = info["lanes_per_row"], info["chunks_per_lane"], info["vector_width"]
+                assert info["rows_per_wave"] * G * info["edge_slots"] == 64
+                assert G * CH * V * info["grid_y"] >= F
+                assert (info["grid_x"] - info["long_row_workgroups"]) * 4 * info["rows_per_wave"] >= N
+
+
+def test_column_slicing_option_only_narrows():
+    base = es.es_spmm_launch_info(1000, 9000, 128, 8, "bucket", opts=dict(lanes_per_row=-1))
     assert base["lanes_per_row"] == 32 and base["grid_y"] == 1
-    es.es_spmm_set_lanes_per_row(8)
-    sliced = es.es_spmm_launch_info(1000, 9000, 128, 8, "bucket")
+    sliced = es.es_spmm_launch_info(1000, 9000, 128, 8, "bucket", opts=dict(lanes_per_row=8))
     assert sliced["lanes_per_row"] == 8 and sliced["chunks_per_lane"] == 1 and sliced["grid_y"] == 4
     _check(sliced, 1000, 128, False)
-    wide = es.es_spmm_launch_info(1000, 9000, 16, 8, "bucket")          # already narrower than 8 lanes
-    assert wide["lanes_per_row"] == 4 and wide["grid_y"] == 1
-    bwd = es.es_spmm_launch_info(1000, 9000, 128, 8, "bucket", backward=True)
+    wide = es.es_spmm_launch_info(1000, 9000, 16, 8, "bucket", opts=dict(lanes_per_row=8))
+    assert wide["lanes_per_row"] == 4 and wide["grid_y"] == 1           # already narrower than 8 lanes
+    bwd = es.es_spmm_launch_info(1000, 9000, 128, 8, "bucket", backward=True, opts=dict(lanes_per_row=8))
     assert bwd["lanes_per_row"] == 64                                   # the transposed product ignores it
-    with pytest.raises(es.EsSpmmError):
-        es.es_spmm_set_lanes_per_row(12)
-    es.es_spmm_set_lanes_per_row(0)
 
 
 def test_bad_sizes_are_rejected():
