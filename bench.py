@@ -236,19 +236,18 @@ def log_rows(tag, rows):
 # --------------------------------------------------------------------------
 # CPU baseline: the oracle as it stands, on the GPU machine's host cores
 # --------------------------------------------------------------------------
-def cpu_baseline(dw, calls, target_seconds=12.0):
-    """The oracle on a bounded random subset of rows of the same workload, every
-    call of the sweep, at all cores and then (a quarter of the rows) on one core.
-    GB/s of the same B_eff byte count as `value`."""
+def cpu_baseline(dw, calls, target_seconds=12.0, max_passes=6):
+    """The oracle, as it stands, on the same workload: every call of the sweep on
+    a random subset of rows sized from a short probe so that about
+    `target_seconds` of CPU work are timed (whole passes over all rows, repeated,
+    when the host is fast enough), at all cores; then the same on one core with a
+    proportionally smaller subset.  GB/s of the same B_eff byte count as `value`."""
     import numpy as np
     import oracle
     w = dw.w
     Xh = w.X if tuple(dw.X.shape) == tuple(w.X.shape) else dw.X.cpu().numpy()
-    work = sum(dw.nnz_kept(m, W) for m, W in calls) * dw.F
     cores = oracle.threads()
-    frac = min(1.0, target_seconds * 0.35e9 * cores / max(work, 1))   # ~0.35 G fp64 FMA / s / core assumed
-    nrows = max(1, int(dw.N * frac))
-    rows = np.sort(np.random.default_rng(0).choice(dw.N, size=nrows, replace=False)).astype(np.int64)
+    order = np.random.default_rng(0).permutation(dw.N).astype(np.int64)
 
     def run(rows_):
         total = 0
@@ -259,17 +258,28 @@ def cpu_baseline(dw, calls, target_seconds=12.0):
             total += algorithmic_bytes(rows_.size, kept, dw.F)
         return total, time.perf_counter() - t0
 
-    total, dt = run(rows)
-    out = {"value": round(total / dt / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
-           "seconds": round(dt, 2),
-           "sample": f"{nrows} random rows of {dw.N} ({100.0 * nrows / dw.N:.2f}%), every call of the sweep, "
-                     f"fp64 accumulation, B_eff bytes of those rows"}
-    rows1 = rows[:: max(1, 4 * cores // 4)] if cores > 1 else rows[::4]
-    oracle.set_threads(1)
-    total1, dt1 = run(rows1)
+    def sized(threads):
+        oracle.set_threads(threads)
+        probe = np.sort(order[:max(1, dw.N // 200)])
+        _, dt = run(probe)                                        # 0.5 % of the rows sizes the sample
+        frac = min(1.0, target_seconds / max(dt, 1e-3) / 200.0)
+        rows = np.sort(order[:max(1, int(dw.N * frac))])
+        passes = 1 if frac < 1.0 else int(min(max_passes, max(1, target_seconds / max(dt * 200.0, 1e-3))))
+        total = dt_sum = 0.0
+        for _ in range(passes):
+            b, dt = run(rows)
+            total += b
+            dt_sum += dt
+        return total / dt_sum / 1e9, dt_sum, rows.size, passes
+
+    v, dt, nrows, passes = sized(cores)
+    out = {"value": round(v, 3), "unit": "GB/s", "cores": cores, "kind": "oracle", "seconds": round(dt, 2),
+           "sample": f"{passes} pass(es) over {nrows} random rows of {dw.N} ({100.0 * nrows / dw.N:.2f}%), every "
+                     f"call of the sweep, fp64 accumulation, B_eff bytes of those rows"}
+    v1, dt1, nrows1, passes1 = sized(1)
     oracle.set_threads(cores)
-    out["single_core_value"] = round(total1 / dt1 / 1e9, 3)
-    out["single_core_sample"] = f"{rows1.size} of those rows, {dt1:.1f} s"
+    out["single_core_value"] = round(v1, 3)
+    out["single_core_sample"] = f"{passes1} pass(es) over {nrows1} rows, {dt1:.1f} s"
     return out
 
 

@@ -71,10 +71,15 @@ def per_call(rows, counter, order):
     return {k: sum(v) / len(v) for k, v in acc.items()}
 
 
-def kernel_mean(rows, counter, needle, first=None):
+def kernel_mean(rows, counter, needle, first=None, largest=None):
+    """Mean of `counter` over the dispatches whose kernel name holds `needle`:
+    all of them, the first `first`, or the `largest` largest readings (the 1 GiB
+    calibration copies among the small copies the framework issues)."""
     v = [float(r["Counter_Value"]) for r in rows if r["Counter_Name"] == counter and needle in r["Kernel_Name"]]
     if first:
         v = v[:first]
+    if largest:
+        v = sorted(v)[-largest:]
     return sum(v) / len(v) if v else None
 
 
@@ -112,8 +117,8 @@ def main() -> int:
 
     fetch, write = counter_rows(d, "fetch"), counter_rows(d, "write")
     l2, lds = counter_rows(d, "l2"), counter_rows(d, "lds")
-    cf = kernel_mean(fetch, "FETCH_SIZE", "copyBuffer")
-    cw = kernel_mean(write, "WRITE_SIZE", "copyBuffer")
+    cf = kernel_mean(fetch, "FETCH_SIZE", "copyBuffer", largest=3)
+    cw = kernel_mean(write, "WRITE_SIZE", "copyBuffer", largest=3)
     ff, fw = GIB_KIB / cf, GIB_KIB / cw
     out.append("## Traffic leaving the L2s (TCC_EA), two runs\n")
     out.append("`rocprofv3 --pmc FETCH_SIZE -d <dir> -o t --output-format csv -- python3 bench.py --main-only "
