@@ -222,7 +222,10 @@ typedef struct {
                                     256-entry segments that several workgroups sum
                                     with atomic adds (load balance for skewed degree
                                     distributions); any positive value             */
-    int32_t reserved;            /* must be 0                                       */
+    int32_t column_partition;    /* es_spmm_ws only: 1 = run the column-partitioned
+                                    product whenever it applies (a workspace is given,
+                                    mode is not ES_BUCKET, N >= 512), -1 = never, 0 =
+                                    the library decides from N, F, W and nnz / N      */
 } es_launch_opts_t;
 
 /*
@@ -235,6 +238,36 @@ int es_spmm_ex(const int32_t* rowptr, const int32_t* colidx, const float* vals,
                int32_t W, int32_t mode, uint64_t seed, int32_t norm,
                const es_launch_opts_t* opts, void* stream);
 
+/*
+ * es_spmm_ws -- es_spmm_ex with a caller-owned workspace, which lets the library
+ * run the column-partitioned form of the product.  Stage 2 of Algorithm 1
+ * (Section 4.3) gathers one row of X per kept entry; on a graph with hundreds of
+ * entries per row and an X several times larger than a 4 MB L2 nearly every
+ * gather misses.  The partitioned form cuts the columns of A into 8 equal
+ * ranges, lets each of the chip's 8 XCDs multiply only the entries of "its"
+ * range -- so it only ever touches one eighth of X -- and builds every row of Y
+ * in 8 stream-ordered launches (the first stores, the others add).  It is used
+ * for ES_FULL and ES_FASTRAND when the library (or opts->column_partition)
+ * decides so.  A row's share of a column range is found by binary search in its
+ * column ids, so the locality is there for rows stored in increasing column
+ * order (the usual CSR); for any other order the result is still the same
+ * product -- the eight pieces always tile the row -- only the locality is lost.
+ * Same sampled entries as es_spmm; Y differs only by fp32 summation order and
+ * is bit-reproducible.
+ *   workspace        device memory, 16-byte aligned, at least
+ *                    es_spmm_workspace_bytes(N) bytes; contents on entry are
+ *                    irrelevant, contents on return are unspecified.  NULL or
+ *                    too small: the call runs exactly as es_spmm_ex.
+ * Calls that share a workspace must be ordered (same stream).
+ */
+size_t es_spmm_workspace_bytes(int64_t N);
+
+int es_spmm_ws(const int32_t* rowptr, const int32_t* colidx, const float* vals,
+               const float* X, float* Y,
+               int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy,
+               int32_t W, int32_t mode, uint64_t seed, int32_t norm,
+               const es_launch_opts_t* opts, void* workspace, size_t workspace_bytes, void* stream);
+
 /* es_spmm_backward_ex -- es_spmm_backward with per-call launch options. */
 int es_spmm_backward_ex(const int32_t* rowptr, const int32_t* colidx, const float* vals,
                         const float* dY, float* dX,
@@ -243,7 +276,8 @@ int es_spmm_backward_ex(const int32_t* rowptr, const int32_t* colidx, const floa
                         const es_launch_opts_t* opts, void* stream);
 
 /*
- * es_spmm_launch_info -- the launch shape es_spmm_ex (backward == 0) or
+ * es_spmm_launch_info -- the launch shape es_spmm_ws (backward == 0; without a
+ * workspace, es_spmm_ex runs the same shape with column_ranges = 1) or
  * es_spmm_backward_ex (backward != 0) would pick for these sizes and options
  * (`opts` may be NULL), without launching anything and without a GPU.
  * `aligned16`: both matrices are 16-byte aligned.  The shape is how Section
@@ -263,6 +297,9 @@ typedef struct {
     int32_t long_row_threshold;  /* rows keeping more entries are split             */
     int64_t long_row_workgroups; /* leading workgroups that serve such rows (or 0)  */
     int64_t grid_x, grid_y;      /* launch grid, 256 threads per workgroup          */
+    int32_t column_ranges;       /* 8: es_spmm_ws with a sufficient workspace would run
+                                    the column-partitioned product (grid_x then is the
+                                    grid of each of its 8 launches); 1: it would not  */
 } es_launch_info_t;
 
 int es_spmm_launch_info(int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W,

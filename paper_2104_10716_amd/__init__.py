@@ -25,6 +25,8 @@ from .binding import (  # noqa: F401
     es_spmm_status_string,
     es_spmm_tile_slots,
     es_spmm_validate_csr,
+    es_spmm_workspace_bytes,
+    es_spmm_ws,
     library_path,
     load_library,
 )

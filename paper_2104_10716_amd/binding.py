@@ -15,7 +15,7 @@ NORMS = {"none": ES_NORM_NONE, "mean": ES_NORM_MEAN, "rsqrt": ES_NORM_RSQRT, "re
 
 class es_launch_opts_t(ctypes.Structure):
     _fields_ = [("rows_per_wave", ctypes.c_int32), ("lanes_per_row", ctypes.c_int32),
-                ("long_row_threshold", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("long_row_threshold", ctypes.c_int32), ("column_partition", ctypes.c_int32)]
 
 
 class es_launch_info_t(ctypes.Structure):
@@ -24,7 +24,7 @@ class es_launch_info_t(ctypes.Structure):
                 ("rows_per_wave", ctypes.c_int32), ("edge_slots", ctypes.c_int32),
                 ("loads_in_flight", ctypes.c_int32), ("tile_slots_per_row", ctypes.c_int32),
                 ("long_row_threshold", ctypes.c_int32), ("long_row_workgroups", ctypes.c_int64),
-                ("grid_x", ctypes.c_int64), ("grid_y", ctypes.c_int64)]
+                ("grid_x", ctypes.c_int64), ("grid_y", ctypes.c_int64), ("column_ranges", ctypes.c_int32)]
 
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -70,6 +70,10 @@ def load_library():
     lib.es_spmm_ex.argtypes = lib.es_spmm_norm.argtypes[:-1] + [optp, vp]
     lib.es_spmm_backward_ex.restype = ctypes.c_int
     lib.es_spmm_backward_ex.argtypes = lib.es_spmm_ex.argtypes
+    lib.es_spmm_ws.restype = ctypes.c_int
+    lib.es_spmm_ws.argtypes = lib.es_spmm_ex.argtypes[:-1] + [vp, ctypes.c_size_t, vp]
+    lib.es_spmm_workspace_bytes.restype = ctypes.c_size_t
+    lib.es_spmm_workspace_bytes.argtypes = [ctypes.c_int64]
     lib.es_spmm_sample_edges.restype = ctypes.c_int
     lib.es_spmm_sample_edges.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                          ctypes.c_uint64, ctypes.c_int32, vp, vp, vp]
@@ -203,6 +207,29 @@ def es_spmm_ex(rowptr, colidx, vals, X, Y, W: int, mode, seed: int = 0, norm="no
                         _stream_ptr(stream))
     if rc != 0:
         raise EsSpmmError(rc, "es_spmm_ex")
+    return Y
+
+
+def es_spmm_workspace_bytes(N: int) -> int:
+    return int(load_library().es_spmm_workspace_bytes(int(N)))
+
+
+def es_spmm_ws(rowptr, colidx, vals, X, Y, W: int, mode, seed: int = 0, norm="none", opts=None,
+               workspace=None, F: Optional[int] = None, stream=None, nnz: Optional[int] = None):
+    """es_spmm_ex with a caller-owned workspace (a device tensor of at least
+    es_spmm_workspace_bytes(N) bytes, any dtype), which enables the column-partitioned product."""
+    lib = load_library()
+    args = _spmm_args(rowptr, colidx, vals, X, Y, F, nnz)
+    nm = NORMS[norm] if isinstance(norm, str) else int(norm)
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        if not workspace.is_cuda or not workspace.is_contiguous():
+            raise ValueError("workspace must be a contiguous device tensor")
+        ws_ptr, ws_bytes = workspace.data_ptr() or None, workspace.numel() * workspace.element_size()
+    rc = lib.es_spmm_ws(*args, int(W), _mode(mode), int(seed) & 0xFFFFFFFFFFFFFFFF, nm, _opts_ptr(opts),
+                        ws_ptr, ws_bytes, _stream_ptr(stream))
+    if rc != 0:
+        raise EsSpmmError(rc, "es_spmm_ws")
     return Y
 
 

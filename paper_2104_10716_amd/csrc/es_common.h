@@ -18,6 +18,8 @@ constexpr int kLongScanRows = 1024;                   // rows one long-row workg
 constexpr int kLongSplit = 16;                        // workgroups sharing those rows
 constexpr int kLongSeg = 256;                         // slots per long-row segment (<= kTileSlots)
 constexpr int kLongMin = 64;                          // smallest long-row threshold the host picks
+constexpr int kParts = kNumXcd;                       // column ranges of the partitioned product
+constexpr int kPartLongPiece = 256;                   // pieces above this many entries start first
 static_assert(kLongSplit % kNumXcd == 0, "long-row workgroups must not shift the XCD phase");
 
 struct Args {
@@ -34,6 +36,10 @@ struct Args {
     uint32_t nblocks;          // workgroups that carry rows
     uint32_t blocks_per_xcd;   // ceil(nblocks / 8)
     uint32_t long_blocks;      // leading workgroups that run the long-row part
+    // column-partitioned product only
+    const int32_t* cuts;       // [N x kParts]: row r's piece of column range j starts at entry cuts[r][j]
+    int32_t part_cols;         // columns per range, ceil(N / kParts)
+    int32_t phase;             // 0 .. kParts-1: which row range each XCD serves in this launch
 };
 
 }  // namespace

@@ -36,6 +36,7 @@
 #include "es_sampler.h"
 #include "es_tile.h"
 #include "es_fused_kernel.h"
+#include "es_part_kernel.h"
 #include "es_aux_kernels.h"
 
 namespace {
@@ -137,13 +138,15 @@ struct Overrides {
     int logR = -1;             // rows_per_wave as a power of two, -1 = heuristic
     int G = 0;                 // lanes_per_row cap, 0 = heuristic, -1 = never slice
     int32_t long_k = 0;        // long-row threshold, 0 = heuristic
+    int partition = 0;         // column-partitioned product: 0 = heuristic, 1 = on, -1 = off
 };
 
 int parse_opts(const es_launch_opts_t* opts, Overrides* ov)
 {
     *ov = Overrides();
     if (!opts) return ES_OK;
-    if (opts->reserved != 0) return ES_ERR_INVALID_ARG;
+    if (opts->column_partition < -1 || opts->column_partition > 1) return ES_ERR_INVALID_ARG;
+    ov->partition = opts->column_partition;
     const int32_t rpw = opts->rows_per_wave;
     if (rpw != 0) {
         if (rpw < 1 || rpw > 64 || (rpw & (rpw - 1))) return ES_ERR_INVALID_ARG;
@@ -182,6 +185,7 @@ struct Plan {
     int64_t per_xcd;           // row workgroups per XCD
     int64_t grid_x, grid_y;    // launch grid (long-row workgroups included in grid_x)
     int64_t long_blocks;       // leading long-row workgroups
+    bool partition;            // column-partitioned product (kParts phases, needs a workspace)
 };
 
 int check_sizes(int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W, int32_t mode,
@@ -196,8 +200,34 @@ int check_sizes(int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int
 
 // Launch shape for N >= 1 rows.  `aligned`: F and both row strides are
 // multiples of 4 and both matrices are 16-byte aligned.
+// Bytes of workspace the column-partitioned product needs for N rows.
+size_t part_workspace_bytes(int64_t N)
+{
+    return (size_t)N * kParts * sizeof(int32_t);
+}
+
+// Whether to run the column-partitioned product.  It pays when a row's piece
+// inside one column range is long enough to amortise the extra pass over Y
+// (kept entries per row well above kParts) and when an XCD's eighth of the
+// column slice of X comes near the size of its L2 while the whole slice does
+// not fit: then most gathers hit the L2 instead of missing it.
+bool pick_partition(int64_t N, double mean_kept, int32_t mode, int cols_per_block, int force)
+{
+    if (mode == ES_BUCKET) return false;       // first-W entries crowd into the lowest column range
+    if (N < kParts * 64) return false;
+    if (force > 0) return true;
+    if (force < 0) return false;
+    // FastRand has to walk all W slots of a row once per column range to find the
+    // ones that fall inside it; measured, that costs more than the locality
+    // returns (config-3 graph, W = 256: 0.8x), so it is only run on request
+    if (mode == ES_FASTRAND) return false;
+    if (mean_kept < 128.0) return false;
+    const double share = (double)N * cols_per_block * 4.0 / kParts;
+    return share >= 1.0e6 && share <= 12.0e6;
+}
+
 int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool aligned, bool backward,
-              const Overrides& ov, Plan* p)
+              const Overrides& ov, bool have_workspace, Plan* p)
 {
     Shape s = pick_shape(F, aligned);
     if (backward) {                                        // see launch_backward
@@ -242,14 +272,46 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
     const bool may_be_long = mode == ES_FULL || W > p->long_k;
     p->long_blocks = may_be_long ? ((N + kLongScanRows - 1) / kLongScanRows) * kLongSplit : 0;
     p->grid_x = p->per_xcd * kNumXcd + p->long_blocks;
+    p->partition = !backward && have_workspace &&
+                   pick_partition(N, mean, mode, cols_per_block, ov.partition);
+    if (p->partition) {
+        // a wave serves kPartGroups consecutive row groups; every launch sweeps the
+        // rows twice, pieces above long_k first (es_part_kernel.h)
+        p->long_k = ov.long_k > 0 ? ov.long_k : kPartLongPiece;
+        const int64_t rows_per_part_block = rows_per_block * kPartGroups;
+        p->nblocks = (N + rows_per_part_block - 1) / rows_per_part_block;
+        p->per_xcd = (p->nblocks + kNumXcd - 1) / kNumXcd;
+        p->long_blocks = p->per_xcd * kNumXcd;
+        p->grid_x = 2 * p->long_blocks;
+    }
     if (p->grid_x > INT32_MAX || p->grid_y > 65535) return ES_ERR_UNSUPPORTED;
     return ES_OK;
+}
+
+template <int G, int CH, int VEC, bool ALIGNED>
+hipError_t launch_partitioned(Args a, dim3 grid, int32_t* cuts, hipStream_t st)
+{
+    a.cuts = cuts;
+    a.part_cols = (int32_t)((a.N + kParts - 1) / kParts);
+    const uint32_t cb = (uint32_t)((a.N * kParts + kBlockThreads - 1) / kBlockThreads);
+    hipLaunchKernelGGL(es_cuts_kernel, dim3(cb), dim3(kBlockThreads), 0, st, a.rowptr, a.colidx, a.N,
+                       a.part_cols, cuts);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    for (int phase = 0; phase < kParts; ++phase) {
+        a.phase = phase;
+        hipLaunchKernelGGL((es_spmm_part_kernel<G, CH, VEC, ALIGNED>), grid, dim3(kBlockThreads), 0, st, a);
+        err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
+    return hipSuccess;
 }
 
 // Shared host path of es_spmm_norm (X -> Y) and es_spmm_backward (dY -> dX).
 int es_run(const int32_t* rowptr, const int32_t* colidx, const float* vals, const float* X, float* Y,
            int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W, int32_t mode,
-           uint64_t seed, int32_t norm, bool backward, const es_launch_opts_t* opts, void* stream)
+           uint64_t seed, int32_t norm, bool backward, const es_launch_opts_t* opts, void* workspace,
+           size_t workspace_bytes, void* stream)
 {
     const int bad = check_sizes(N, nnz, F, ldx, ldy, W, mode, norm);
     if (bad != ES_OK) return bad;
@@ -264,8 +326,10 @@ int es_run(const int32_t* rowptr, const int32_t* colidx, const float* vals, cons
     const bool aligned = (F % 4 == 0) && (ldx % 4 == 0) && (ldy % 4 == 0) &&
                          (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
                          (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
+    if (workspace && reinterpret_cast<uintptr_t>(workspace) % 16) return ES_ERR_INVALID_ARG;
+    const bool have_ws = workspace && workspace_bytes >= part_workspace_bytes(N);
     Plan p;
-    const int rc = make_plan(N, nnz, F, W, mode, aligned, backward, ov, &p);
+    const int rc = make_plan(N, nnz, F, W, mode, aligned, backward, ov, have_ws, &p);
     if (rc != ES_OK) return rc;
     const Shape& s = p.s;
 
@@ -276,13 +340,16 @@ int es_run(const int32_t* rowptr, const int32_t* colidx, const float* vals, cons
     a.mode = mode; a.logR = p.logR; a.norm = norm; a.long_k = p.long_k;
     a.nblocks = (uint32_t)p.nblocks; a.blocks_per_xcd = (uint32_t)p.per_xcd;
     a.long_blocks = (uint32_t)p.long_blocks;
+    a.cuts = nullptr; a.part_cols = 0; a.phase = 0;
 
     const dim3 grid((uint32_t)p.grid_x, (uint32_t)p.grid_y);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t err = hipErrorInvalidValue;
-#define ES_CASE(G_, CH_, V_, A_)                                                   \
-    if (!backward && s.G == G_ && s.CH == CH_ && s.vec == V_ && s.aligned == A_)   \
-        err = launch_forward<G_, CH_, V_, A_>(a, grid, st);
+#define ES_CASE(G_, CH_, V_, A_)                                                          \
+    if (!backward && s.G == G_ && s.CH == CH_ && s.vec == V_ && s.aligned == A_)          \
+        err = p.partition                                                                 \
+                  ? launch_partitioned<G_, CH_, V_, A_>(a, grid, static_cast<int32_t*>(workspace), st) \
+                  : launch_forward<G_, CH_, V_, A_>(a, grid, st);
     ES_CASE(4, 1, 4, true) ES_CASE(8, 1, 4, true) ES_CASE(16, 1, 4, true) ES_CASE(32, 1, 4, true)
     ES_CASE(64, 1, 4, true) ES_CASE(64, 2, 4, true) ES_CASE(64, 4, 4, true)
     ES_CASE(4, 1, 4, false) ES_CASE(8, 1, 4, false) ES_CASE(16, 1, 4, false) ES_CASE(32, 1, 4, false)
@@ -333,7 +400,7 @@ int es_spmm_norm(const int32_t* rowptr, const int32_t* colidx, const float* vals
                  int32_t mode, uint64_t seed, int32_t norm, void* stream)
 {
     return es_run(rowptr, colidx, vals, X, Y, N, nnz, F, ldx, ldy, W, mode, seed, norm, false, nullptr,
-                  stream);
+                  nullptr, 0, stream);
 }
 
 int es_spmm_ex(const int32_t* rowptr, const int32_t* colidx, const float* vals, const float* X,
@@ -341,7 +408,18 @@ int es_spmm_ex(const int32_t* rowptr, const int32_t* colidx, const float* vals, 
                int32_t mode, uint64_t seed, int32_t norm, const es_launch_opts_t* opts, void* stream)
 {
     return es_run(rowptr, colidx, vals, X, Y, N, nnz, F, ldx, ldy, W, mode, seed, norm, false, opts,
-                  stream);
+                  nullptr, 0, stream);
+}
+
+size_t es_spmm_workspace_bytes(int64_t N) { return N < 0 ? 0 : part_workspace_bytes(N); }
+
+int es_spmm_ws(const int32_t* rowptr, const int32_t* colidx, const float* vals, const float* X,
+               float* Y, int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W,
+               int32_t mode, uint64_t seed, int32_t norm, const es_launch_opts_t* opts, void* workspace,
+               size_t workspace_bytes, void* stream)
+{
+    return es_run(rowptr, colidx, vals, X, Y, N, nnz, F, ldx, ldy, W, mode, seed, norm, false, opts,
+                  workspace, workspace_bytes, stream);
 }
 
 int es_spmm_backward(const int32_t* rowptr, const int32_t* colidx, const float* vals,
@@ -349,7 +427,7 @@ int es_spmm_backward(const int32_t* rowptr, const int32_t* colidx, const float* 
                      int32_t ldx, int32_t W, int32_t mode, uint64_t seed, int32_t norm, void* stream)
 {
     return es_run(rowptr, colidx, vals, dY, dX, N, nnz, F, ldy, ldx, W, mode, seed, norm, true, nullptr,
-                  stream);
+                  nullptr, 0, stream);
 }
 
 int es_spmm_backward_ex(const int32_t* rowptr, const int32_t* colidx, const float* vals,
@@ -358,7 +436,7 @@ int es_spmm_backward_ex(const int32_t* rowptr, const int32_t* colidx, const floa
                         const es_launch_opts_t* opts, void* stream)
 {
     return es_run(rowptr, colidx, vals, dY, dX, N, nnz, F, ldy, ldx, W, mode, seed, norm, true, opts,
-                  stream);
+                  nullptr, 0, stream);
 }
 
 int es_spmm_launch_info(int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W,
@@ -374,7 +452,7 @@ int es_spmm_launch_info(int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t 
     if (N == 0) return ES_ERR_INVALID_ARG;
     const bool aligned = aligned16 && (F % 4 == 0) && (ldx % 4 == 0) && (ldy % 4 == 0);
     Plan p;
-    const int rc = make_plan(N, nnz, F, W, mode, aligned, backward != 0, ov, &p);
+    const int rc = make_plan(N, nnz, F, W, mode, aligned, backward != 0, ov, true, &p);
     if (rc != ES_OK) return rc;
     info->vector_width = p.s.vec;
     info->aligned = p.s.aligned ? 1 : 0;
@@ -388,6 +466,7 @@ int es_spmm_launch_info(int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t 
     info->long_row_workgroups = p.long_blocks;
     info->grid_x = p.grid_x;
     info->grid_y = p.grid_y;
+    info->column_ranges = p.partition ? kParts : 1;
     return ES_OK;
 }
 

@@ -52,6 +52,7 @@ template <bool ALIGNED> struct Pack<4, ALIGNED> {
         v.z = fmaf(a, x.v.z, v.z); v.w = fmaf(a, x.v.w, v.w);
     }
     __device__ __forceinline__ void scale(float f) { v.x *= f; v.y *= f; v.z *= f; v.w *= f; }
+    __device__ __forceinline__ void add(const Pack& o) { v.x += o.v.x; v.y += o.v.y; v.z += o.v.z; v.w += o.v.w; }
     __device__ __forceinline__ void add_xor(int mask)
     {
         v.x += __shfl_xor(v.x, mask, kWaveSize); v.y += __shfl_xor(v.y, mask, kWaveSize);
@@ -66,6 +67,7 @@ template <bool ALIGNED> struct Pack<1, ALIGNED> {
     __device__ __forceinline__ void atomic_add(float* p, int) const { unsafeAtomicAdd(p, v); }
     __device__ __forceinline__ void fma(float a, const Pack& x) { v = fmaf(a, x.v, v); }
     __device__ __forceinline__ void scale(float f) { v *= f; }
+    __device__ __forceinline__ void add(const Pack& o) { v += o.v; }
     __device__ __forceinline__ void add_xor(int mask) { v += __shfl_xor(v, mask, kWaveSize); }
 };
 

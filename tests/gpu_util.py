@@ -23,7 +23,16 @@ class DeviceCSR:
         import paper_2104_10716_amd as es
         ldy = self.F if ldy is None else ldy
         Y = torch.full((self.N, ldy), float("nan"), dtype=torch.float32, device=self.X.device)
-        if opts is not None:
+        if opts is not None and "workspace" in opts:
+            # es_spmm_ws: the value is a device tensor, or True = allocate one of the size the library asks for
+            opts = dict(opts)
+            ws = opts.pop("workspace")
+            if ws is True:
+                ws = torch.full((es.es_spmm_workspace_bytes(self.N) // 4,), -7, dtype=torch.int32,
+                                device=self.X.device)
+            es.es_spmm_ws(self.rowptr, self.colidx, self.vals, self.X, Y, W, mode, seed,
+                          "none" if norm is None else norm, opts, ws, F=self.F)
+        elif opts is not None:
             es.es_spmm_ex(self.rowptr, self.colidx, self.vals, self.X, Y, W, mode, seed,
                           "none" if norm is None else norm, opts, F=self.F)
         elif norm is None:

@@ -103,7 +103,7 @@ def test_argument_checks_answer_on_the_host(lib):
         assert call_ex(entry, lanes_per_row=12) == -1
         assert call_ex(entry, lanes_per_row=-2) == -1
         assert call_ex(entry, long_row_threshold=-1) == -1
-        assert call_ex(entry, reserved=5) == -1
+        assert call_ex(entry, column_partition=2) == -1
         assert entry(fake, fake, None, fake, fake, 0, 0, 4, 4, 4, 2, 1, 0, 0, None, None) == 0   # N == 0
 
 

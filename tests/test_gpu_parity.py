@@ -89,6 +89,102 @@ def test_column_slicing_override(es, F):
                                      what=f"lanes={lanes} thr={thr} F={F} {mode} W={W}")
 
 
+@pytest.mark.parametrize("F,ldx", [(1, 1), (4, 4), (17, 20), (41, 41), (64, 64), (100, 128), (128, 128),
+                                   (260, 260), (602, 602)])
+def test_column_partitioned_product(es, F, ldx):
+    """es_spmm_ws with the column-partitioned product forced on: eight launches
+    that each add one column range's share of every row must give the oracle's
+    product, for every launch shape, row factor and output stride."""
+    from gpu_util import DeviceCSR, check_against_oracle
+    n = 1531                                   # not a multiple of 8, of the row blocks or of any tile
+    rowptr, colidx, vals, X = _random_graph(n, 40.0, seed=300 + F, F=F, ldx=ldx)
+    d = DeviceCSR(rowptr, colidx, vals, X, F=F)
+    maxdeg = int(np.diff(rowptr).max())
+    _say(f"column-partitioned F={F} ldx={ldx} maxdeg={maxdeg}")
+    for rpw in (0, 1, 4, 64):
+        for lanes, thr in ((0, 0), (8, 0), (0, 2), (0, 10 ** 6)):      # thr: pieces above it go to the first sweep
+            opts = dict(workspace=True, column_partition=1, rows_per_wave=rpw, lanes_per_row=lanes,
+                        long_row_threshold=thr)
+            info = es.es_spmm_launch_info(n, colidx.size, F, 8, "fastrand", ldx=ldx, ldy=ldx + 4,
+                                          opts={k: v for k, v in opts.items() if k != "workspace"})
+            assert info["column_ranges"] == 8 and info["long_row_workgroups"] * 2 == info["grid_x"]
+            check_against_oracle(d, 0, "full", what=f"partitioned full F={F} rpw={rpw} lanes={lanes}", opts=opts)
+            for W in (1, 7, 30, maxdeg - 1, maxdeg + 5):
+                for seed in (0, 12345):
+                    check_against_oracle(d, W, "fastrand", seed, ldy=ldx + 4 if F % 4 == 0 else None,
+                                         norm="mean" if seed else None, opts=opts,
+                                         what=f"partitioned fastrand F={F} W={W} seed={seed} rpw={rpw} lanes={lanes}")
+            # Bucket never takes the partitioned path: same call, plain product
+            check_against_oracle(d, 7, "bucket", 0, what=f"bucket with a workspace F={F}", opts=opts)
+    # a workspace that is too small, or none: the plain product
+    import torch
+    small = torch.empty(8, dtype=torch.int32, device="cuda:0")
+    check_against_oracle(d, 0, "full", what="workspace too small", opts=dict(workspace=small, column_partition=1))
+    check_against_oracle(d, 0, "full", what="no workspace", opts=dict(workspace=None, column_partition=1))
+    assert es.es_spmm_workspace_bytes(n) == 4 * 8 * n
+
+
+def test_column_partitioned_product_edge_cases(es):
+    """Rows out of column order (the pieces found by binary search must still
+    tile every row), duplicate columns, empty rows, all entries in one column
+    range, long rows spanning several tiles."""
+    import torch
+    from gpu_util import DeviceCSR, check_against_oracle
+    rng = np.random.default_rng(8)
+    n = 2000
+    rowptr, colidx, vals, X = _random_graph(n, 60.0, seed=77, F=32, empty_frac=0.2)
+    force = dict(workspace=True, column_partition=1)
+    # (a) one single row out of order
+    ci = colidx.copy()
+    r = int(np.argmax(np.diff(rowptr) > 5))
+    ci[[rowptr[r], rowptr[r] + 3]] = ci[[rowptr[r] + 3, rowptr[r]]]
+    d = DeviceCSR(rowptr, ci, vals, X)
+    for mode, W in (("full", 0), ("fastrand", 9), ("fastrand", 200)):
+        check_against_oracle(d, W, mode, 3, what=f"one row out of order {mode} W={W}", opts=force)
+    # (b) every row shuffled
+    ci = colidx.copy()
+    for r in range(n):
+        rng.shuffle(ci[rowptr[r]:rowptr[r + 1]])
+    d = DeviceCSR(rowptr, ci, vals, X)
+    for mode, W in (("full", 0), ("fastrand", 9)):
+        check_against_oracle(d, W, mode, 3, what=f"shuffled rows {mode} W={W}", opts=force)
+    # (c) duplicate columns inside rows (non-decreasing, not strictly increasing)
+    ci = colidx.copy()
+    dup = rng.random(colidx.size) < 0.3
+    dup[rowptr[:-1][np.diff(rowptr) > 0]] = False         # never a row's first entry
+    for p in np.nonzero(dup)[0]:
+        ci[p] = ci[p - 1]                                  # in order: runs of equal columns
+    d = DeviceCSR(rowptr, ci, vals, X)
+    for mode, W in (("full", 0), ("fastrand", 9)):
+        check_against_oracle(d, W, mode, 3, what=f"duplicate columns {mode} W={W}", opts=force)
+    # (d) all columns inside one range (range 5 of 8), and rows of 0 .. 3000 entries
+    lengths = [0, 1, 63, 64, 65, 511, 512, 513, 577, 1154, 3000, 2999] * 60
+    N = len(lengths)
+    lo, hi = 5 * ((N + 7) // 8), min(N, 6 * ((N + 7) // 8))
+    cols = [np.sort(rng.integers(lo, hi, size=L)) for L in lengths]
+    rp = np.zeros(N + 1, dtype=np.int32)
+    rp[1:] = np.cumsum(lengths)
+    cc = np.concatenate(cols).astype(np.int32)
+    vv = rng.standard_normal(cc.size).astype(np.float32)
+    XX = rng.uniform(-1, 1, (N, 16)).astype(np.float32)
+    d = DeviceCSR(rp, cc, vv, XX)
+    for rpw in (0, 1, 8):
+        opts = dict(force, rows_per_wave=rpw)
+        check_against_oracle(d, 0, "full", what=f"one column range, full, rpw={rpw}", opts=opts)
+        for W in (16, 512, 600, 1153, 2999):
+            check_against_oracle(d, W, "fastrand", 5, what=f"one column range, fastrand W={W} rpw={rpw}", opts=opts)
+    # (e) the workspace is reused across calls without being cleared in between
+    ws = torch.full((es.es_spmm_workspace_bytes(n) // 4,), 0x7FFFFFFF, dtype=torch.int32, device="cuda:0")
+    d = DeviceCSR(rowptr, colidx, vals, X)
+    for rep in range(2):
+        check_against_oracle(d, 0, "full", what="shared workspace, sorted graph", opts=dict(force, workspace=ws))
+        ci2 = colidx.copy()
+        for r in range(n):
+            rng.shuffle(ci2[rowptr[r]:rowptr[r + 1]])
+        check_against_oracle(DeviceCSR(rowptr, ci2, vals, X), 0, "full", what="shared workspace, shuffled graph",
+                             opts=dict(force, workspace=ws))
+
+
 def test_randomised_shapes(es):
     """Seeded sweep over random combinations of graph size, degree, F, row
     strides, W, mode, seed, row factor and the per-call launch options, forward
@@ -114,11 +210,15 @@ def test_randomised_shapes(es):
         thr = int(rng.choice([0, 0, 1, 3, 40]))
         lanes = int(rng.choice([0, 0, 0, 4, 16]))
         opts = dict(rows_per_wave=rpw, long_row_threshold=thr, lanes_per_row=lanes)
-        what = (f"case {case}: n={n} avg={avg} F={F} ld={F + pad} {mode} W={W} seed={seed} norm={norm} "
+        part = int(rng.choice([0, 0, 1, -1]))
+        if part:
+            opts.update(workspace=True, column_partition=part)
+        what = (f"case {case}: part={part} n={n} avg={avg} F={F} ld={F + pad} {mode} W={W} seed={seed} norm={norm} "
                 f"rpw={rpw} thr={thr} lanes={lanes}")
         _say(what)
         ldy = F + int(rng.choice([0, 0, 2, 4]))
         check_against_oracle(d, W, mode, seed, ldy=ldy, norm=norm, what=what, opts=opts)
+        opts.pop("workspace", None)
         check_backward_against_oracle(d, W, mode, seed, norm, what="backward " + what, opts=opts)
         if mode != "full":
             check_edges(d, W, mode, seed, int(rng.choice([0, 1, 4, -1])), what="edges " + what)
@@ -214,7 +314,7 @@ def test_degenerate_inputs(es):
     with pytest.raises(es.EsSpmmError):
         es.es_spmm_backward(du.rowptr, du.colidx, du.vals, du.X, Yk, 0, "bucket")
     for bad_opts in (dict(rows_per_wave=3), dict(rows_per_wave=128), dict(lanes_per_row=12),
-                     dict(long_row_threshold=-1), dict(reserved=1)):
+                     dict(long_row_threshold=-1), dict(column_partition=-2)):
         with pytest.raises(es.EsSpmmError):
             es.es_spmm_ex(du.rowptr, du.colidx, du.vals, du.X, Yk, 4, "bucket", 0, "none", bad_opts)
         with pytest.raises(es.EsSpmmError):
@@ -690,6 +790,25 @@ def test_config3_social_like_every_width(es, mode):
     for W in w.Ws:
         worst = check_every_element(d, W, mode, 0, what=f"cfg3 {mode} W={W}")
         _say(f"cfg3 {mode} W={W}: max normalised error {worst:.2e} over all {w.N} x {w.F} elements")
+
+
+def test_config3_column_partitioned(es):
+    """Config 3 through es_spmm_ws (the library itself chooses the column-
+    partitioned product here): every element against the oracle, and the result
+    is bit-identical from launch to launch."""
+    import torch
+    from gpu_util import check_every_element
+    w, d = _cfg3_device()
+    info = es.es_spmm_launch_info(w.N, w.nnz, w.F, 0, "full")
+    assert info["column_ranges"] == 8, info
+    ws = torch.empty(es.es_spmm_workspace_bytes(w.N) // 4, dtype=torch.int32, device="cuda:0")
+    for mode, W in (("full", 0), ("fastrand", 256), ("fastrand", 2304)):
+        opts = dict(workspace=ws, column_partition=0 if mode == "full" else 1)   # FastRand: only on request
+        worst = check_every_element(d, W, mode, 0, what=f"cfg3 partitioned {mode} W={W}", opts=opts)
+        _say(f"cfg3 es_spmm_ws {mode} W={W}: max normalised error {worst:.2e} over all {w.N} x {w.F} elements")
+    a = d.run(0, "full", opts=dict(workspace=ws))
+    b = d.run(0, "full", opts=dict(workspace=ws))
+    assert torch.equal(a, b)
 
 
 def test_config3_social_like_edge_lists(es):

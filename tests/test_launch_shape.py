@@ -23,6 +23,9 @@ def _check(info, N, F, backward):
     assert G * CH * V * (info["grid_y"] - 1) < F          # ... by no more column blocks than needed
     rows_per_workgroup = 4 * R
     row_groups = info["grid_x"] - info["long_row_workgroups"]
+    if info["column_ranges"] == 8:                        # a wave serves 4 row groups; two sweeps per launch
+        rows_per_workgroup *= 4
+        assert info["long_row_workgroups"] == row_groups
     assert row_groups % 8 == 0                            # one equal share per XCD
     assert row_groups * rows_per_workgroup >= N
     assert info["long_row_workgroups"] % 8 == 0
@@ -48,8 +51,13 @@ def test_shape_invariants_over_sizes_and_widths(backward):
 
 def test_long_rows_are_only_possible_when_the_long_part_is_launched():
     for (N, nnz), F in itertools.product(SHAPES, (16, 64, 128, 41)):
-        full = es.es_spmm_launch_info(N, nnz, F, 0, "full")
+        full = es.es_spmm_launch_info(N, nnz, F, 0, "full", opts=dict(column_partition=-1))
         assert full["long_row_workgroups"] > 0            # nnz is only a hint: never gated by it
+        assert full["column_ranges"] == 1
+        auto = es.es_spmm_launch_info(N, nnz, F, 0, "full")
+        # the column-partitioned product sweeps its rows twice per launch (long pieces first)
+        if auto["column_ranges"] == 8:
+            assert auto["long_row_workgroups"] * 2 == auto["grid_x"]
         for W in (1, 16, 128, 512):
             s = es.es_spmm_launch_info(N, nnz, F, W, "fastrand")
             assert s["long_row_threshold"] >= 512 and s["long_row_workgroups"] == 0
@@ -70,7 +78,7 @@ def test_options_are_honoured_and_clamped():
     # an all-zero struct is the same as no struct
     assert es.es_spmm_launch_info(1000, 5000, 64, 8, "bucket", opts={}) == base
     for bad in (dict(rows_per_wave=3), dict(rows_per_wave=-1), dict(lanes_per_row=12), dict(lanes_per_row=-2),
-                dict(long_row_threshold=-4), dict(reserved=1)):
+                dict(long_row_threshold=-4), dict(column_partition=-2)):
         with pytest.raises(es.EsSpmmError):
             es.es_spmm_launch_info(1000, 5000, 64, 8, "bucket", opts=bad)
 
@@ -82,12 +90,13 @@ def test_option_grid_keeps_the_shape_invariants():
             for backward in (False, True):
                 info = es.es_spmm_launch_info(N, nnz, F, 64, mode, backward=backward, opts=opts)
                 assert info["long_row_threshold"] >= (thr if thr else 64)
-                if thr:
+                if thr and info["column_ranges"] == 1:
                     assert info["long_row_threshold"] == thr
                 G, CH, V = info["lanes_per_row"], info["chunks_per_lane"], info["vector_width"]
                 assert info["rows_per_wave"] * G * info["edge_slots"] == 64
                 assert G * CH * V * info["grid_y"] >= F
-                assert (info["grid_x"] - info["long_row_workgroups"]) * 4 * info["rows_per_wave"] >= N
+                groups = 4 if info["column_ranges"] == 8 else 1
+                assert (info["grid_x"] - info["long_row_workgroups"]) * 4 * info["rows_per_wave"] * groups >= N
 
 
 def test_column_slicing_option_only_narrows():
@@ -100,6 +109,26 @@ def test_column_slicing_option_only_narrows():
     assert wide["lanes_per_row"] == 4 and wide["grid_y"] == 1           # already narrower than 8 lanes
     bwd = es.es_spmm_launch_info(1000, 9000, 128, 8, "bucket", backward=True, opts=dict(lanes_per_row=8))
     assert bwd["lanes_per_row"] == 64                                   # the transposed product ignores it
+
+
+def test_column_partition_choice():
+    """Dense graph whose eighth of X is near an L2: partitioned for the exact
+    product and for wide FastRand, never for Bucket, never for sparse graphs or
+    for tables far beyond the L2s; the option forces it either way."""
+    dense = (233_000, 113_134_823)
+    assert es.es_spmm_launch_info(*dense, 64, 0, "full")["column_ranges"] == 8
+    assert es.es_spmm_launch_info(*dense, 64, 256, "fastrand")["column_ranges"] == 1      # only on request
+    assert es.es_spmm_launch_info(*dense, 64, 256, "fastrand", opts=dict(column_partition=1))["column_ranges"] == 8
+    assert es.es_spmm_launch_info(*dense, 64, 256, "bucket")["column_ranges"] == 1
+    assert es.es_spmm_launch_info(*dense, 64, 256, "bucket", opts=dict(column_partition=1))["column_ranges"] == 1
+    assert es.es_spmm_launch_info(*dense, 64, 0, "full", opts=dict(column_partition=-1))["column_ranges"] == 1
+    assert es.es_spmm_launch_info(170_000, 2_370_240, 128, 0, "full")["column_ranges"] == 1      # 14 per row
+    assert es.es_spmm_launch_info(2_450_000, 119_569_270, 128, 0, "full")["column_ranges"] == 1  # X far too big
+    forced = es.es_spmm_launch_info(170_000, 2_370_240, 128, 0, "full", opts=dict(column_partition=1))
+    assert forced["column_ranges"] == 8 and forced["long_row_workgroups"] * 2 == forced["grid_x"]
+    assert forced["long_row_workgroups"] % 8 == 0
+    assert es.es_spmm_launch_info(100, 5000, 64, 0, "full", opts=dict(column_partition=1))["column_ranges"] == 1
+    assert es.es_spmm_launch_info(*dense, 64, 0, "full", backward=True)["column_ranges"] == 1
 
 
 def test_bad_sizes_are_rejected():
