@@ -50,7 +50,8 @@ typedef enum {
 typedef enum {
     ES_OK = 0,
     ES_ERR_INVALID_ARG = -1,  /* null pointer, negative size, ld < F, W < 1, bad mode */
-    ES_ERR_UNSUPPORTED = -2,  /* shape outside what the kernels cover               */
+    ES_ERR_UNSUPPORTED = -2,  /* shape outside what the kernels cover, or N above the
+                                 capacity of es_spmm_static_ws                     */
     ES_ERR_LAUNCH = -3        /* the HIP runtime rejected the launch                */
 } es_status_t;
 
@@ -267,6 +268,30 @@ int es_spmm_ws(const int32_t* rowptr, const int32_t* colidx, const float* vals,
                int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy,
                int32_t W, int32_t mode, uint64_t seed, int32_t norm,
                const es_launch_opts_t* opts, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * es_spmm_static_ws -- es_spmm_ws for callers that cannot allocate device
+ * memory for a workspace: code running under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, rules and results
+ * as es_spmm_ws, except that the workspace is a fixed array inside the library
+ * (static device memory of ES_SPMM_STATIC_WS_MAX_ROWS * 32 bytes, held on every
+ * GPU the library runs on until the process ends).  The call allocates and
+ * frees nothing, on the host or on the device.
+ *   N > ES_SPMM_STATIC_WS_MAX_ROWS  ->  ES_ERR_UNSUPPORTED, nothing is launched
+ *                                       (use es_spmm_ws with a workspace of your own)
+ * Every call on a GPU shares that GPU's array: calls that may overlap in time
+ * on one GPU (different streams, different threads) race on it and must be
+ * ordered by the caller; calls on one stream are ordered by the stream.  The
+ * array keeps the previous call's contents; every call overwrites the part it
+ * reads, so nothing needs clearing in between.
+ */
+#define ES_SPMM_STATIC_WS_MAX_ROWS 1048576
+
+int es_spmm_static_ws(const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                      const float* X, float* Y,
+                      int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy,
+                      int32_t W, int32_t mode, uint64_t seed, int32_t norm,
+                      const es_launch_opts_t* opts, void* stream);
 
 /* es_spmm_backward_ex -- es_spmm_backward with per-call launch options. */
 int es_spmm_backward_ex(const int32_t* rowptr, const int32_t* colidx, const float* vals,

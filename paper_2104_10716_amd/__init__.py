@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     ES_BUCKET,
     ES_FASTRAND,
     ES_FULL,
+    ES_SPMM_STATIC_WS_MAX_ROWS,
     MODES,
     NORMS,
     EsSpmmError,
@@ -25,6 +26,7 @@ from .binding import (  # noqa: F401
     es_spmm_status_string,
     es_spmm_tile_slots,
     es_spmm_validate_csr,
+    es_spmm_static_ws,
     es_spmm_workspace_bytes,
     es_spmm_ws,
     library_path,

@@ -72,6 +72,8 @@ def load_library():
     lib.es_spmm_backward_ex.argtypes = lib.es_spmm_ex.argtypes
     lib.es_spmm_ws.restype = ctypes.c_int
     lib.es_spmm_ws.argtypes = lib.es_spmm_ex.argtypes[:-1] + [vp, ctypes.c_size_t, vp]
+    lib.es_spmm_static_ws.restype = ctypes.c_int
+    lib.es_spmm_static_ws.argtypes = lib.es_spmm_ex.argtypes
     lib.es_spmm_workspace_bytes.restype = ctypes.c_size_t
     lib.es_spmm_workspace_bytes.argtypes = [ctypes.c_int64]
     lib.es_spmm_sample_edges.restype = ctypes.c_int
@@ -230,6 +232,23 @@ def es_spmm_ws(rowptr, colidx, vals, X, Y, W: int, mode, seed: int = 0, norm="no
                         ws_ptr, ws_bytes, _stream_ptr(stream))
     if rc != 0:
         raise EsSpmmError(rc, "es_spmm_ws")
+    return Y
+
+
+ES_SPMM_STATIC_WS_MAX_ROWS = 1048576
+
+
+def es_spmm_static_ws(rowptr, colidx, vals, X, Y, W: int, mode, seed: int = 0, norm="none", opts=None,
+                      F: Optional[int] = None, stream=None, nnz: Optional[int] = None):
+    """es_spmm_ws on the library's own static workspace (allocates nothing; at most
+    ES_SPMM_STATIC_WS_MAX_ROWS rows; calls on one GPU must not overlap in time)."""
+    lib = load_library()
+    args = _spmm_args(rowptr, colidx, vals, X, Y, F, nnz)
+    nm = NORMS[norm] if isinstance(norm, str) else int(norm)
+    rc = lib.es_spmm_static_ws(*args, int(W), _mode(mode), int(seed) & 0xFFFFFFFFFFFFFFFF, nm,
+                               _opts_ptr(opts), _stream_ptr(stream))
+    if rc != 0:
+        raise EsSpmmError(rc, "es_spmm_static_ws")
     return Y
 
 

@@ -30,6 +30,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "es_spmm.h"
 
 #include "es_common.h"
@@ -39,11 +41,37 @@
 #include "es_part_kernel.h"
 #include "es_aux_kernels.h"
 
+// Workspace of es_spmm_static_ws: the cuts array of the column-partitioned
+// product for up to ES_SPMM_STATIC_WS_MAX_ROWS rows, in static device memory.
+// In host code this name is only a handle for hipGetSymbolAddress; the address
+// kernels receive is the per-device pointer static_scratch_address() returns.
+static __device__ __align__(256) unsigned char scratch[(size_t)ES_SPMM_STATIC_WS_MAX_ROWS * kParts * sizeof(int32_t)];
+
 namespace {
 
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
+constexpr int kMaxDevices = 64;
+
+// Device address of `scratch` on the current device (every GPU holds its own
+// copy of the array at its own address); looked up once per device.
+int static_scratch_address(void** out)
+{
+    static std::mutex mu;
+    static void* address[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ES_ERR_LAUNCH;
+    std::lock_guard<std::mutex> guard(mu);
+    if (!address[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return ES_ERR_LAUNCH;
+        address[dev] = p;
+    }
+    *out = address[dev];
+    return ES_OK;
+}
+
 struct Shape {
     int vec, G, CH;
     bool aligned;
@@ -372,7 +400,9 @@ const char* es_spmm_status_string(int status)
     switch (status) {
         case ES_OK: return "ES_OK";
         case ES_ERR_INVALID_ARG: return "ES_ERR_INVALID_ARG: null pointer, negative size, ld < F, W < 1 or unknown mode";
-        case ES_ERR_UNSUPPORTED: return "ES_ERR_UNSUPPORTED: shape outside what the kernels cover";
+        case ES_ERR_UNSUPPORTED:
+            return "ES_ERR_UNSUPPORTED: shape outside what the kernels cover (or more rows than "
+                   "es_spmm_static_ws holds a workspace for: use es_spmm_ws)";
         case ES_ERR_LAUNCH: return "ES_ERR_LAUNCH: the HIP runtime rejected the launch";
         default: return "unknown es_spmm status";
     }
@@ -420,6 +450,27 @@ int es_spmm_ws(const int32_t* rowptr, const int32_t* colidx, const float* vals, 
 {
     return es_run(rowptr, colidx, vals, X, Y, N, nnz, F, ldx, ldy, W, mode, seed, norm, false, opts,
                   workspace, workspace_bytes, stream);
+}
+
+int es_spmm_static_ws(const int32_t* rowptr, const int32_t* colidx, const float* vals, const float* X,
+                      float* Y, int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W,
+                      int32_t mode, uint64_t seed, int32_t norm, const es_launch_opts_t* opts, void* stream)
+{
+    // argument errors first (as every entry point), then the capacity of the
+    // static array, then -- the first thing that touches the GPU -- its address
+    const int bad = check_sizes(N, nnz, F, ldx, ldy, W, mode, norm);
+    if (bad != ES_OK) return bad;
+    Overrides ov;
+    const int bad_opts = parse_opts(opts, &ov);
+    if (bad_opts != ES_OK) return bad_opts;
+    if (N > ES_SPMM_STATIC_WS_MAX_ROWS) return ES_ERR_UNSUPPORTED;
+    if (N == 0) return ES_OK;
+    if (!rowptr || !X || !Y || (nnz > 0 && !colidx)) return ES_ERR_INVALID_ARG;
+    void* ws = nullptr;
+    const int rc = static_scratch_address(&ws);
+    if (rc != ES_OK) return rc;
+    return es_run(rowptr, colidx, vals, X, Y, N, nnz, F, ldx, ldy, W, mode, seed, norm, false, opts, ws,
+                  sizeof(scratch), stream);
 }
 
 int es_spmm_backward(const int32_t* rowptr, const int32_t* colidx, const float* vals,

@@ -107,6 +107,21 @@ def test_argument_checks_answer_on_the_host(lib):
         assert entry(fake, fake, None, fake, fake, 0, 0, 4, 4, 4, 2, 1, 0, 0, None, None) == 0   # N == 0
 
 
+def test_static_workspace_entry_point_checks_its_capacity_on_the_host(lib):
+    import paper_2104_10716_amd as es
+    fake = ctypes.c_void_p(0x1000)
+    big = es.ES_SPMM_STATIC_WS_MAX_ROWS + 1
+    call = lambda N, **kw: lib.es_spmm_static_ws(fake, fake, None, fake, kw.get("Y", fake), N, 16, 4, 4, 4, 2, 1,
+                                                 0, 0, None, None)
+    assert call(big) == -2                                  # more rows than the static array holds
+    assert "es_spmm_ws" in es.es_spmm_status_string(-2)
+    assert call(-1) == -1 and call(8, Y=None) == -1          # argument errors come first
+    assert call(0) == 0
+    assert es.es_spmm_workspace_bytes(es.ES_SPMM_STATIC_WS_MAX_ROWS) == 32 * es.ES_SPMM_STATIC_WS_MAX_ROWS
+    text = open(HEADER).read()
+    assert f"#define ES_SPMM_STATIC_WS_MAX_ROWS {es.ES_SPMM_STATIC_WS_MAX_ROWS}" in text
+
+
 def test_no_process_wide_settings_are_exported(lib):
     """The ABI is stateless: launch overrides travel with the call."""
     for name in ("es_spmm_set_rows_per_wave", "es_spmm_set_lanes_per_row", "es_spmm_set_long_row_threshold"):
