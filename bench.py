@@ -113,6 +113,10 @@ class DeviceWorkload:
         self.vals = torch.from_numpy(w.vals).to(dev)
         self.X = torch.from_numpy(w.X).to(dev) if X is None else X
         self.Y = torch.empty((self.N, self.F), dtype=torch.float32, device=dev)
+        # caller-owned workspace of es_spmm_ws (lets the library run its column-partitioned
+        # product where it decides to); allocated once, outside every timed region
+        import paper_2104_10716_amd as es
+        self.ws = torch.empty(max(1, es.es_spmm_workspace_bytes(self.N) // 4), dtype=torch.int32, device=dev)
         self._distinct = {}
 
     def calls(self, Ws):
@@ -155,7 +159,8 @@ class DeviceWorkload:
 
     def launch(self, mode, W, seed=0):
         import paper_2104_10716_amd as es
-        es.es_spmm(self.rowptr, self.colidx, self.vals, self.X, self.Y, W, mode, seed, F=self.F)
+        es.es_spmm_ws(self.rowptr, self.colidx, self.vals, self.X, self.Y, W, mode, seed, "none", None, self.ws,
+                      F=self.F)
 
 
 def call_label(mode, W):

@@ -31,6 +31,7 @@ struct Args {
     int64_t N;
     uint64_t seed;
     int32_t F, ldx, ldy, W, mode, logR;
+    uint32_t stride_units;     // row stride of the gathered (scattered) matrix in RowKey units
     int32_t long_k;            // rows keeping more entries go to the long-row part  
     int32_t norm;              // es_norm_t: row factor applied before the store
     uint32_t nblocks;          // workgroups that carry rows

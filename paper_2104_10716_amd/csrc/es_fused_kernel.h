@@ -12,7 +12,7 @@ namespace {
 // columns (blockIdx.y selects the block).  Rows that keep more than long_k
 // entries are left to the long-row part and not stored here.
 // ---------------------------------------------------------------------------
-template <int G, int CH, int VEC, bool ALIGNED, bool BACKWARD>
+template <int G, int CH, int VEC, bool ALIGNED, bool BACKWARD, bool WIDE>
 __device__ __forceinline__ void row_block(const Args& a, uint32_t vb, uint2* lds)
 {
     constexpr int LOG_G = ilog2(G);
@@ -53,9 +53,9 @@ __device__ __forceinline__ void row_block(const Args& a, uint32_t vb, uint2* lds
         if (k > 0) load_row_chunks<G, CH, VEC, ALIGNED>(a, r, n, k_row, cols, dy);
         for (int t0 = 0; t0 < k; t0 += T) {
             const int count = min(k - t0, T);
-            stage_tile(sampler, t, team, count, base, a.colidx, a.vals, tile);
+            stage_tile<ALIGNED, WIDE>(sampler, t, team, count, base, a.colidx, a.vals, a.stride_units, tile);
             wave_lds_fence();
-            scatter_tile<G, CH, VEC, ALIGNED>(tile, count, e, E, a.Y, a.ldy, cols, dy);
+            scatter_tile<G, CH, VEC, ALIGNED, WIDE>(tile, count, e, E, a.Y, a.ldy, cols, dy);
             wave_lds_fence();
         }
         return;
@@ -67,9 +67,9 @@ __device__ __forceinline__ void row_block(const Args& a, uint32_t vb, uint2* lds
 
     for (int t0 = 0; t0 < k; t0 += T) {
         const int count = min(k - t0, T);
-        stage_tile(sampler, t, team, count, base, a.colidx, a.vals, tile);
+        stage_tile<ALIGNED, WIDE>(sampler, t, team, count, base, a.colidx, a.vals, a.stride_units, tile);
         wave_lds_fence();
-        consume_tile<G, CH, VEC, ALIGNED>(tile, count, e, E, a.X, a.ldx, cols, acc);
+        consume_tile<G, CH, VEC, ALIGNED, WIDE>(tile, count, e, E, a.X, a.ldx, cols, acc);
         wave_lds_fence();
     }
 
@@ -105,7 +105,7 @@ struct LongScratch {
     int wave_total[kWavesPerBlock];
 };
 
-template <int G, int CH, int VEC, bool ALIGNED, bool BACKWARD>
+template <int G, int CH, int VEC, bool ALIGNED, bool BACKWARD, bool WIDE>
 __device__ __forceinline__ void long_block(const Args& a, uint32_t bx, uint32_t by, uint2* lds,
                                            LongScratch& sc)
 {
@@ -176,19 +176,19 @@ __device__ __forceinline__ void long_block(const Args& a, uint32_t bx, uint32_t 
 
         RowSampler sampler;
         sampler.init(a.mode, a.seed, r, (uint32_t)n, (uint32_t)a.W, (uint32_t)(t0 + lane), kWaveSize);
-        stage_tile(sampler, lane, kWaveSize, count, base, a.colidx, a.vals, tile);
+        stage_tile<ALIGNED, WIDE>(sampler, lane, kWaveSize, count, base, a.colidx, a.vals, a.stride_units, tile);
         wave_lds_fence();
         if (BACKWARD) {
             P dy[CH];
             load_row_chunks<G, CH, VEC, ALIGNED>(a, r, n, k, cols, dy);
-            scatter_tile<G, CH, VEC, ALIGNED>(tile, count, e, E, a.Y, a.ldy, cols, dy);
+            scatter_tile<G, CH, VEC, ALIGNED, WIDE>(tile, count, e, E, a.Y, a.ldy, cols, dy);
             wave_lds_fence();
             continue;
         }
         P acc[CH];
 #pragma unroll
         for (int ch = 0; ch < CH; ++ch) acc[ch].zero();
-        consume_tile<G, CH, VEC, ALIGNED>(tile, count, e, E, a.X, a.ldx, cols, acc);
+        consume_tile<G, CH, VEC, ALIGNED, WIDE>(tile, count, e, E, a.X, a.ldx, cols, acc);
         wave_lds_fence();
 #pragma unroll
         for (int m = G; m < kWaveSize; m <<= 1) {
@@ -216,21 +216,21 @@ __device__ __forceinline__ void long_block(const Args& a, uint32_t bx, uint32_t 
 // workgroup b to XCD b % 8; long_blocks is a multiple of 8) walks one
 // contiguous range of rows.
 // ---------------------------------------------------------------------------
-template <int G, int CH, int VEC, bool ALIGNED, bool BACKWARD>
+template <int G, int CH, int VEC, bool ALIGNED, bool BACKWARD, bool WIDE>
 __global__ void __launch_bounds__(kBlockThreads) es_spmm_kernel(const Args a)
 {
     __shared__ uint2 lds[kWavesPerBlock * kWaveTileStride];
     __shared__ LongScratch long_scratch;
 
     if (blockIdx.x < a.long_blocks) {
-        long_block<G, CH, VEC, ALIGNED, BACKWARD>(a, blockIdx.x / kLongSplit, blockIdx.x % kLongSplit,
+        long_block<G, CH, VEC, ALIGNED, BACKWARD, WIDE>(a, blockIdx.x / kLongSplit, blockIdx.x % kLongSplit,
                                                   lds, long_scratch);
         return;
     }
     const uint32_t b = blockIdx.x - a.long_blocks;
     const uint32_t vb = (b % kNumXcd) * a.blocks_per_xcd + b / kNumXcd;
     if (vb >= a.nblocks) return;
-    row_block<G, CH, VEC, ALIGNED, BACKWARD>(a, vb, lds);
+    row_block<G, CH, VEC, ALIGNED, BACKWARD, WIDE>(a, vb, lds);
 }
 
 // Zero-fills an [N x F] matrix with row stride ld (the transposed product

@@ -26,12 +26,12 @@ namespace {
 // multiplied exactly once.  Rows stored in increasing column order -- the usual
 // CSR -- get the locality; other rows only lose it.
 //
-// A piece is short (an eighth of a row), so the chain "row pointers -> entries
-// -> rows of X" would leave a wave waiting most of the time.  A wave therefore
-// serves kPartGroups consecutive row groups: all their row pointers and cuts
-// are requested at once, and the first entries of group i+1 are requested
-// before the rows of X of group i, so that only the gathers stay on the
-// critical path.
+// A piece is short (an eighth of a row), so per-piece instructions and the chain
+// "row pointers -> entries -> rows of X" weigh far more than in the plain
+// kernel.  A wave therefore serves kPartGroups consecutive rows, one at a time
+// with all 64 lanes: their row pointers and cuts are requested at once, and the
+// first entries of row i+1 are requested before the rows of X of row i, so that
+// only the gathers stay on the critical path.
 //
 // Degrees are skewed, so some pieces are a hundred times longer than the typical
 // one, and a wave that starts such a piece near the end of a launch would keep
@@ -41,7 +41,7 @@ namespace {
 // once), the trailing half serves the rest.  The long pieces thus start first
 // and run beside the bulk of the work; each piece still has exactly one owner.
 // ---------------------------------------------------------------------------
-constexpr int kPartGroups = 4;       // consecutive row groups one wave serves
+constexpr int kPartGroups = 4;       // consecutive rows one wave serves
 constexpr int kPartPrefetch = 2;     // entries per lane requested one group ahead
 
 // Eight lanes per row: lane j finds the first entry whose column is >= j * part_cols.
@@ -72,7 +72,7 @@ es_cuts_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ c
     if (r < N) cuts[r * kParts + j] = lo;
 }
 
-// Entries of one row group requested ahead of time.
+// Entries of one row's piece requested ahead of time.
 struct AheadEntries {
     int32_t col[kPartPrefetch];
     float val[kPartPrefetch];
@@ -80,43 +80,41 @@ struct AheadEntries {
 };
 
 // Row part of phase a.phase: workgroup `vb` of the row grid, column range `part`.
-template <int G, int CH, int VEC, bool ALIGNED>
+// One row per wave at a time (the path is only taken for rows with hundreds of
+// entries), all 64 lanes on the row: E = 64 / G edge slots.
+template <int G, int CH, int VEC, bool ALIGNED, bool WIDE>
 __device__ __forceinline__ void part_row_block(const Args& a, uint32_t vb, int part, bool long_sweep,
                                                uint2* lds)
 {
     constexpr int LOG_G = ilog2(G);
+    constexpr int E = kWaveSize / G;             // edge slots per row
     constexpr int B = kPartGroups;
     constexpr int PF = kPartPrefetch;
+    constexpr int T = kTileSlots;
     using P = Pack<VEC, ALIGNED>;
+    using K = RowKey<ALIGNED, WIDE>;
 
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
-    const int logR = a.logR;
-    const int team = kWaveSize >> logR;          // lanes per row
-    const int rs = lane >> (6 - logR);           // row slot inside the wave
-    const int t = lane & (team - 1);             // lane inside the team
-    const int e = t >> LOG_G;                    // edge slot
-    const int l = t & (G - 1);                   // column lane
-    const int E = team >> LOG_G;                 // edge slots per row (>= 1)
-    const int T = kTileSlots >> logR;            // tile slots per row
-    uint2* tile = lds + wave * kWaveTileStride + rs * (T + 1);
-    const unsigned long long team_mask =
-        (team == kWaveSize ? ~0ull : ((1ull << team) - 1ull)) << (rs * team);
+    const int e = lane >> LOG_G;                 // edge slot
+    const int l = lane & (G - 1);                // column lane
+    uint2* tile = lds + wave * kWaveTileStride;
     const unsigned long long below_me = (1ull << lane) - 1ull;
     const bool accumulate = a.phase != 0;        // phase 0 starts every row from zero
+    const bool fastrand = a.mode == ES_FASTRAND;
 
     LaneCols<G, CH, VEC, ALIGNED> cols;
     cols.init(blockIdx.y * (G * CH * VEC), l, a.F);
 
-    // ---- row pointers and cuts of all B groups, one round trip ---------------
-    const int64_t group0 = ((int64_t)vb * kWavesPerBlock + wave) * B;
+    // ---- row pointers and cuts of all B rows, one round trip -----------------
+    const int64_t row0 = ((int64_t)vb * kWavesPerBlock + wave) * B;
     int32_t base[B], n[B], lo[B], hi[B];
     int32_t slots[B];          // sampler slots to walk for the piece; 0 when the other sweep owns it
     bool mine[B];
     bool any = false;
 #pragma unroll
     for (int i = 0; i < B; ++i) {
-        const int64_t r = ((group0 + i) << logR) + rs;
+        const int64_t r = row0 + i;
         base[i] = 0; n[i] = 0; lo[i] = 0; hi[i] = 0;
         if (r < a.N) {
             base[i] = a.rowptr[r];
@@ -125,26 +123,25 @@ __device__ __forceinline__ void part_row_block(const Args& a, uint32_t vb, int p
             lo[i] = cr[part];
             hi[i] = (part + 1 < kParts) ? cr[part + 1] : n[i];
         }
-        const bool strided = a.mode == ES_FASTRAND && n[i] > a.W;
+        const bool strided = fastrand && n[i] > a.W;
         const int piece = hi[i] - lo[i];
         const int k_row = kept_count(a.mode, n[i], a.W);
         mine[i] = r < a.N && (min(piece, k_row) > a.long_k) == long_sweep;
         slots[i] = !mine[i] ? 0 : strided ? (piece > 0 ? k_row : 0) : piece;
         any = any || mine[i];
     }
-    if (!__any(any)) return;                     // (the long sweep's usual case)
+    if (!any) return;                            // wave-uniform (the long sweep's usual case)
 
-    // Requests the first PF entries per lane of group i's piece.  Contiguous
+    // Requests the first PF entries per lane of row i's piece.  Contiguous
     // pieces (exact product, or a row kept whole): entries lo + slot.  FastRand
     // on a longer row: the slots' entry numbers, kept when they fall in [lo, hi).
     auto request = [&](int i, RowSampler& sampler, AheadEntries& ah) {
-        const int64_t r = ((group0 + i) << logR) + rs;
-        const bool strided = a.mode == ES_FASTRAND && n[i] > a.W;
-        if (strided) sampler.init(a.mode, a.seed, r, (uint32_t)n[i], (uint32_t)a.W, (uint32_t)t, (uint32_t)team);
-        else sampler.init(ES_FULL, 0, r, (uint32_t)n[i], 0u, (uint32_t)t, (uint32_t)team);
+        const bool strided = fastrand && n[i] > a.W;
+        if (strided) sampler.init(a.mode, a.seed, row0 + i, (uint32_t)n[i], (uint32_t)a.W, (uint32_t)lane, kWaveSize);
+        else sampler.init(ES_FULL, 0, row0 + i, (uint32_t)n[i], 0u, (uint32_t)lane, kWaveSize);
 #pragma unroll
         for (int j = 0; j < PF; ++j) {
-            const int slot = t + j * team;
+            const int slot = lane + j * kWaveSize;
             ah.keep[j] = false;
             ah.col[j] = 0;
             ah.val[j] = 0.0f;
@@ -161,46 +158,63 @@ __device__ __forceinline__ void part_row_block(const Args& a, uint32_t vb, int p
         }
     };
 
+    // Stages slots [s0, s0 + count) of row i's piece behind the `fill` entries
+    // already in the tile; returns the new fill.  Contiguous pieces keep every
+    // slot, so slot numbers are tile positions; strided ones are packed.
+    auto stage_more = [&](int i, RowSampler& walk, int first, int count, int fill) {
+        const bool strided = fastrand && n[i] > a.W;
+        for (int i0 = first; i0 < count; i0 += kWaveSize) {
+            const bool valid = i0 + lane < count;
+            const int32_t entry = (int32_t)walk.next();
+            const bool keep = valid && (strided ? (entry >= lo[i] && entry < hi[i]) : true);
+            int at = i0 + lane;
+            if (strided) {
+                const unsigned long long m = __ballot(keep);
+                at = fill + __popcll(m & below_me);
+                fill += __popcll(m);
+            }
+            if (keep) {
+                const int64_t p = (int64_t)base[i] + (strided ? entry : lo[i] + entry);
+                const float v = a.vals ? a.vals[p] : 1.0f;
+                tile[at] = make_uint2(K::make(a.colidx[p], a.stride_units), __float_as_uint(v));
+            }
+        }
+        return strided ? fill : count;
+    };
+
     RowSampler sampler;
     AheadEntries ahead;
     request(0, sampler, ahead);
 
 #pragma unroll
     for (int i = 0; i < B; ++i) {
-        const int64_t r = ((group0 + i) << logR) + rs;
-        const bool strided = a.mode == ES_FASTRAND && n[i] > a.W;
+        const int64_t r = row0 + i;
+        const bool strided = fastrand && n[i] > a.W;
         const int k_row = kept_count(a.mode, n[i], a.W);
         float* y = a.Y + r * (int64_t)a.ldy;
 
         // ---- first tile: the entries requested ahead, then the rest of it ------
         const int count0 = min(slots[i], T);
-        int fill = 0;                            // entries in the tile (team-uniform)
+        int fill = 0;                            // entries in the tile (wave-uniform)
 #pragma unroll
         for (int j = 0; j < PF; ++j) {
-            if (j * team < count0) {             // team-uniform
-                const unsigned long long m = __ballot(ahead.keep[j]) & team_mask;
+            if (j * kWaveSize < count0) {
+                int at = lane + j * kWaveSize;
+                if (strided) {
+                    const unsigned long long m = __ballot(ahead.keep[j]);
+                    at = fill + __popcll(m & below_me);
+                    fill += __popcll(m);
+                }
                 if (ahead.keep[j])
-                    tile[fill + __popcll(m & below_me)] =
-                        make_uint2((uint32_t)ahead.col[j], __float_as_uint(ahead.val[j]));
-                fill += __popcll(m);
+                    tile[at] = make_uint2(K::make(ahead.col[j], a.stride_units), __float_as_uint(ahead.val[j]));
             }
         }
+        if (!strided) fill = min(count0, PF * kWaveSize);
         RowSampler walk = sampler;               // continues after the PF slots already taken
-        for (int i0 = PF * team; i0 < count0; i0 += team) {
-            const bool valid = i0 + t < count0;
-            const int32_t entry = (int32_t)walk.next();
-            const bool keep = valid && (strided ? (entry >= lo[i] && entry < hi[i]) : true);
-            const unsigned long long m = __ballot(keep) & team_mask;
-            if (keep) {
-                const int64_t p = (int64_t)base[i] + (strided ? entry : lo[i] + entry);
-                const float v = a.vals ? a.vals[p] : 1.0f;
-                tile[fill + __popcll(m & below_me)] = make_uint2((uint32_t)a.colidx[p], __float_as_uint(v));
-            }
-            fill += __popcll(m);
-        }
+        fill = stage_more(i, walk, PF * kWaveSize, count0, fill);
         wave_lds_fence();
 
-        // ---- the row's earlier partial sums, and the next group's entries ------
+        // ---- the row's earlier partial sums, and the next row's entries --------
         P prev[CH];
 #pragma unroll
         for (int ch = 0; ch < CH; ++ch) prev[ch].zero();
@@ -214,34 +228,22 @@ __device__ __forceinline__ void part_row_block(const Args& a, uint32_t vb, int p
         P acc[CH];
 #pragma unroll
         for (int ch = 0; ch < CH; ++ch) acc[ch].zero();
-        bool touched = fill > 0;                 // team-uniform: the piece holds a kept entry
-        consume_tile<G, CH, VEC, ALIGNED>(tile, fill, e, E, a.X, a.ldx, cols, acc);
+        bool touched = fill > 0;                 // wave-uniform: the piece holds a kept entry
+        consume_tile<G, CH, VEC, ALIGNED, WIDE>(tile, fill, e, E, a.X, a.ldx, cols, acc);
         wave_lds_fence();
 
         // ---- further tiles of a long piece --------------------------------------
         for (int t0 = T; t0 < slots[i]; t0 += T) {
-            const int count = min(slots[i] - t0, T);
-            fill = 0;
-            for (int i0 = 0; i0 < count; i0 += team) {
-                const bool valid = i0 + t < count;
-                const int32_t entry = (int32_t)walk.next();
-                const bool keep = valid && (strided ? (entry >= lo[i] && entry < hi[i]) : true);
-                const unsigned long long m = __ballot(keep) & team_mask;
-                if (keep) {
-                    const int64_t p = (int64_t)base[i] + (strided ? entry : lo[i] + entry);
-                    const float v = a.vals ? a.vals[p] : 1.0f;
-                    tile[fill + __popcll(m & below_me)] = make_uint2((uint32_t)a.colidx[p], __float_as_uint(v));
-                }
-                fill += __popcll(m);
-            }
+            fill = stage_more(i, walk, 0, min(slots[i] - t0, T), 0);
             touched = touched || fill > 0;
             wave_lds_fence();
-            consume_tile<G, CH, VEC, ALIGNED>(tile, fill, e, E, a.X, a.ldx, cols, acc);
+            consume_tile<G, CH, VEC, ALIGNED, WIDE>(tile, fill, e, E, a.X, a.ldx, cols, acc);
             wave_lds_fence();
         }
 
-        // ---- sum the E edge slots of each row, update Y ---------------------------
-        for (int m = G; m < team; m <<= 1) {
+        // ---- sum the E edge slots, update Y ---------------------------------------
+#pragma unroll
+        for (int m = G; m < kWaveSize; m <<= 1) {
 #pragma unroll
             for (int ch = 0; ch < CH; ++ch) acc[ch].add_xor(m);
         }
@@ -265,7 +267,7 @@ __device__ __forceinline__ void part_row_block(const Args& a, uint32_t vb, int p
 // p = b % 8 (hardware deals workgroups round-robin; only the speed depends on
 // it, not the result) and serves column range p for the rows of row range
 // (p + phase) % 8.
-template <int G, int CH, int VEC, bool ALIGNED>
+template <int G, int CH, int VEC, bool ALIGNED, bool WIDE>
 __global__ void __launch_bounds__(kBlockThreads) es_spmm_part_kernel(const Args a)
 {
     __shared__ uint2 lds[kWavesPerBlock * kWaveTileStride];
@@ -276,7 +278,7 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_part_kernel(const Args 
     const uint32_t s = (p + (uint32_t)a.phase) % kNumXcd;
     const uint32_t vb = s * a.blocks_per_xcd + q;
     if (vb >= a.nblocks) return;
-    part_row_block<G, CH, VEC, ALIGNED>(a, vb, (int)p, long_sweep, lds);
+    part_row_block<G, CH, VEC, ALIGNED, WIDE>(a, vb, (int)p, long_sweep, lds);
 }
 
 }  // namespace

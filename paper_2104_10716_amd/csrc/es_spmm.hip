@@ -117,7 +117,7 @@ int pick_logR(const Shape& s, double mean_kept)
     return logR;
 }
 
-template <int G, int CH, int VEC, bool ALIGNED>
+template <int G, int CH, int VEC, bool ALIGNED, bool WIDE>
 hipError_t launch_forward(const Args& a, dim3 grid, hipStream_t st)
 {
     if (a.long_blocks > 0) {
@@ -126,7 +126,7 @@ hipError_t launch_forward(const Args& a, dim3 grid, hipStream_t st)
         const hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
-    hipLaunchKernelGGL((es_spmm_kernel<G, CH, VEC, ALIGNED, false>), grid, dim3(kBlockThreads), 0, st, a);
+    hipLaunchKernelGGL((es_spmm_kernel<G, CH, VEC, ALIGNED, false, WIDE>), grid, dim3(kBlockThreads), 0, st, a);
     return hipGetLastError();
 }
 
@@ -135,7 +135,7 @@ hipError_t launch_forward(const Args& a, dim3 grid, hipStream_t st)
 // consecutive floats of an output row instead of every fourth one, which is
 // what the memory-side atomic units are fastest at (measured 4x over the
 // 128-bit mapping); G is as wide as F allows for the same reason.
-template <int G, int CH>
+template <int G, int CH, bool WIDE>
 hipError_t launch_backward(const Args& a, dim3 grid, hipStream_t st)
 {
     int64_t fb = (a.N * (int64_t)a.F + kBlockThreads * 8 - 1) / (kBlockThreads * 8);
@@ -144,7 +144,7 @@ hipError_t launch_backward(const Args& a, dim3 grid, hipStream_t st)
                        a.ldy);
     const hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL((es_spmm_kernel<G, CH, 1, false, true>), grid, dim3(kBlockThreads), 0, st, a);
+    hipLaunchKernelGGL((es_spmm_kernel<G, CH, 1, false, true, WIDE>), grid, dim3(kBlockThreads), 0, st, a);
     return hipGetLastError();
 }
 
@@ -265,16 +265,41 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
         if (s.G > 64) s.G = 64;
         s.CH = F > 128 ? 4 : F > 64 ? 2 : 1;
     }
-    const int32_t force_G = ov.G;
-    if (!backward && force_G > 0 && s.vec == 4 && force_G < s.G) {
-        s.G = force_G;                                     // narrower column blocks, more of them
+    double mean = (double)nnz / (double)N;                 // mean entries a row keeps
+    const double mean_stored = mean;
+    if (mode != ES_FULL && mean > (double)W) mean = (double)W;
+
+    // Column-partitioned product?  Decided on 64-column slices, its best width.
+    const int slice_cols = F < 64 ? s.G * s.CH * s.vec : 64;
+    p->partition = !backward && have_workspace && pick_partition(N, mean, mode, slice_cols, ov.partition);
+
+    // Column slicing: fewer lanes across the feature columns, the rows swept once
+    // per slice, so that the part of X in use at a time is smaller.  Measured
+    // gains (profiles/): 64-column slices in the partitioned product for F > 64;
+    // 64-column slices on tables beyond ~0.5 GB (the co-purchase graph's
+    // community of X rows then comes nearer to an L2); 32-column slices for
+    // Bucket on rows several times longer than W (its picks crowd into the
+    // lowest-numbered columns).  Elsewhere slicing only re-reads the CSR entries.
+    int slice_G = 0;
+    bool sliced_by_rule = false;
+    if (!backward && s.vec == 4) {
+        if (ov.G > 0) slice_G = ov.G;
+        else if (ov.G == 0) {
+            if (p->partition) slice_G = 16;
+            else if (mode == ES_BUCKET && F >= 64 && mean_stored >= 4.0 * W) slice_G = 8;
+            else if (F >= 128 && (double)N * F * 4.0 >= 512.0e6) slice_G = 16;
+            sliced_by_rule = slice_G > 0 && slice_G < s.G;
+        }
+    }
+    if (slice_G > 0 && slice_G < s.G) {
+        s.G = slice_G;                                     // narrower column blocks, more of them
         s.CH = 1;
     }
     p->s = s;
 
-    double mean = (double)nnz / (double)N;
-    if (mode != ES_FULL && mean > (double)W) mean = (double)W;
     int logR = pick_logR(s, mean);
+    // a slice gathers less per row, so sampled rows share a wave in larger numbers
+    if (sliced_by_rule && mode != ES_FULL && !p->partition && (64 >> (logR + 1)) >= s.G) ++logR;
     const int32_t force_logR = ov.logR;
     if (force_logR >= 0) {
         logR = force_logR;
@@ -300,13 +325,12 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
     const bool may_be_long = mode == ES_FULL || W > p->long_k;
     p->long_blocks = may_be_long ? ((N + kLongScanRows - 1) / kLongScanRows) * kLongSplit : 0;
     p->grid_x = p->per_xcd * kNumXcd + p->long_blocks;
-    p->partition = !backward && have_workspace &&
-                   pick_partition(N, mean, mode, cols_per_block, ov.partition);
     if (p->partition) {
-        // a wave serves kPartGroups consecutive row groups; every launch sweeps the
-        // rows twice, pieces above long_k first (es_part_kernel.h)
+        // a wave serves kPartGroups consecutive rows, one at a time; every launch
+        // sweeps the rows twice, pieces above long_k first (es_part_kernel.h)
+        p->logR = 0;
         p->long_k = ov.long_k > 0 ? ov.long_k : kPartLongPiece;
-        const int64_t rows_per_part_block = rows_per_block * kPartGroups;
+        const int64_t rows_per_part_block = (int64_t)kWavesPerBlock * kPartGroups;
         p->nblocks = (N + rows_per_part_block - 1) / rows_per_part_block;
         p->per_xcd = (p->nblocks + kNumXcd - 1) / kNumXcd;
         p->long_blocks = p->per_xcd * kNumXcd;
@@ -316,7 +340,7 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
     return ES_OK;
 }
 
-template <int G, int CH, int VEC, bool ALIGNED>
+template <int G, int CH, int VEC, bool ALIGNED, bool WIDE>
 hipError_t launch_partitioned(Args a, dim3 grid, int32_t* cuts, hipStream_t st)
 {
     a.cuts = cuts;
@@ -328,7 +352,7 @@ hipError_t launch_partitioned(Args a, dim3 grid, int32_t* cuts, hipStream_t st)
     if (err != hipSuccess) return err;
     for (int phase = 0; phase < kParts; ++phase) {
         a.phase = phase;
-        hipLaunchKernelGGL((es_spmm_part_kernel<G, CH, VEC, ALIGNED>), grid, dim3(kBlockThreads), 0, st, a);
+        hipLaunchKernelGGL((es_spmm_part_kernel<G, CH, VEC, ALIGNED, WIDE>), grid, dim3(kBlockThreads), 0, st, a);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
@@ -373,21 +397,31 @@ int es_run(const int32_t* rowptr, const int32_t* colidx, const float* vals, cons
     const dim3 grid((uint32_t)p.grid_x, (uint32_t)p.grid_y);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t err = hipErrorInvalidValue;
+    // RowKey form: the gathered matrix is X (forward) or dX (backward, the
+    // matrix passed as Y here); its largest row offset in RowKey units must fit 32 bits
+    const int64_t gather_ld = backward ? ldy : ldx;
+    const bool key_aligned = !backward && s.aligned;
+    const int64_t stride_units = key_aligned ? gather_ld / 4 : gather_ld;
+    const bool wide = (uint64_t)N * (uint64_t)stride_units > 0xFFFFFFFFull;
+    a.stride_units = wide ? 0u : (uint32_t)stride_units;
+#define ES_LAUNCH(G_, CH_, V_, A_, W_)                                                              \
+    (p.partition ? launch_partitioned<G_, CH_, V_, A_, W_>(a, grid, static_cast<int32_t*>(workspace), st) \
+                 : launch_forward<G_, CH_, V_, A_, W_>(a, grid, st))
 #define ES_CASE(G_, CH_, V_, A_)                                                          \
     if (!backward && s.G == G_ && s.CH == CH_ && s.vec == V_ && s.aligned == A_)          \
-        err = p.partition                                                                 \
-                  ? launch_partitioned<G_, CH_, V_, A_>(a, grid, static_cast<int32_t*>(workspace), st) \
-                  : launch_forward<G_, CH_, V_, A_>(a, grid, st);
+        err = wide ? ES_LAUNCH(G_, CH_, V_, A_, true) : ES_LAUNCH(G_, CH_, V_, A_, false);
     ES_CASE(4, 1, 4, true) ES_CASE(8, 1, 4, true) ES_CASE(16, 1, 4, true) ES_CASE(32, 1, 4, true)
     ES_CASE(64, 1, 4, true) ES_CASE(64, 2, 4, true) ES_CASE(64, 4, 4, true)
     ES_CASE(4, 1, 4, false) ES_CASE(8, 1, 4, false) ES_CASE(16, 1, 4, false) ES_CASE(32, 1, 4, false)
     ES_CASE(64, 1, 4, false) ES_CASE(64, 2, 4, false) ES_CASE(64, 4, 4, false)
     ES_CASE(4, 1, 1, false)
-#define ES_BWD(G_, CH_) \
-    if (backward && s.G == G_ && s.CH == CH_) err = launch_backward<G_, CH_>(a, grid, st);
+#define ES_BWD(G_, CH_)                         \
+    if (backward && s.G == G_ && s.CH == CH_)   \
+        err = wide ? launch_backward<G_, CH_, true>(a, grid, st) : launch_backward<G_, CH_, false>(a, grid, st);
     ES_BWD(4, 1) ES_BWD(8, 1) ES_BWD(16, 1) ES_BWD(32, 1) ES_BWD(64, 1) ES_BWD(64, 2) ES_BWD(64, 4)
 #undef ES_BWD
 #undef ES_CASE
+#undef ES_LAUNCH
     return err == hipSuccess ? ES_OK : ES_ERR_LAUNCH;
 }
 

@@ -98,24 +98,49 @@ struct LaneCols {
     }
 };
 
+// How a staged column id turns into the address of that row of the dense
+// matrix.  WIDE == false: stage 1 stores the row's offset, column * stride,
+// as a 32-bit count of UNIT floats (UNIT = 4 for 16-byte aligned rows, else 1),
+// so that stage 2 forms an address with one shift-add instead of a 64-bit
+// multiply per gathered row; the host picks this form whenever the largest
+// offset fits 32 bits (matrices up to 64 GB, or 16 GB for unaligned rows).
+// WIDE == true: the column id is stored and multiplied in stage 2.
+template <bool ALIGNED, bool WIDE>
+struct RowKey {
+    static constexpr int UNIT = ALIGNED ? 4 : 1;
+    __device__ __forceinline__ static uint32_t make(int32_t col, uint32_t stride_units)
+    {
+        return WIDE ? (uint32_t)col : (uint32_t)col * stride_units;
+    }
+    __device__ __forceinline__ static const float* row(const float* base, uint32_t key, int64_t stride)
+    {
+        return WIDE ? base + (int64_t)key * stride : base + (size_t)key * UNIT;
+    }
+    __device__ __forceinline__ static float* row(float* base, uint32_t key, int64_t stride)
+    {
+        return WIDE ? base + (int64_t)key * stride : base + (size_t)key * UNIT;
+    }
+};
+
 // Stage 1 of Algorithm 1 for one tile: copy the sampled (column, value) pairs
-// of slots [0, count) into the LDS tile.
+// of slots [0, count) into the LDS tile (the column as its RowKey).
+template <bool ALIGNED, bool WIDE>
 __device__ __forceinline__ void stage_tile(RowSampler& sampler, int t, int team, int count,
                                            int32_t base, const int32_t* __restrict__ colidx,
-                                           const float* __restrict__ vals, uint2* tile)
+                                           const float* __restrict__ vals, uint32_t stride_units, uint2* tile)
 {
     sample_tile(sampler, t, team, count, [&](int slot, uint32_t entry) {
         const int64_t p = (int64_t)base + entry;
         const int32_t c = colidx[p];
         const float v = vals ? vals[p] : 1.0f;
-        tile[slot] = make_uint2((uint32_t)c, __float_as_uint(v));
+        tile[slot] = make_uint2(RowKey<ALIGNED, WIDE>::make(c, stride_units), __float_as_uint(v));
     });
 }
 
 // Stage 2 of Algorithm 1 for one tile: this lane's edge slot e (of E) walks
 // tile entries e, e+E, ... < count, U at a time: U LDS broadcasts, then U*CH
 // independent loads of X, then the FMAs.
-template <int G, int CH, int VEC, bool ALIGNED>
+template <int G, int CH, int VEC, bool ALIGNED, bool WIDE>
 __device__ __forceinline__ void consume_tile(const uint2* tile, int count, int e, int E,
                                              const float* __restrict__ X, int64_t ldx,
                                              const LaneCols<G, CH, VEC, ALIGNED>& cols,
@@ -123,6 +148,7 @@ __device__ __forceinline__ void consume_tile(const uint2* tile, int count, int e
 {
     constexpr int U = 8 / CH;
     using P = Pack<VEC, ALIGNED>;
+    using K = RowKey<ALIGNED, WIDE>;
     int j = e;
     for (; j + (U - 1) * E < count; j += U * E) {            // full batches
         uint2 ed[U];
@@ -131,7 +157,7 @@ __device__ __forceinline__ void consume_tile(const uint2* tile, int count, int e
         P x[U][CH];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const float* xr = X + (int64_t)ed[u].x * ldx;
+            const float* xr = K::row(X, ed[u].x, ldx);
 #pragma unroll
             for (int ch = 0; ch < CH; ++ch) x[u][ch].load(xr + cols.off[ch]);
         }
@@ -154,7 +180,7 @@ __device__ __forceinline__ void consume_tile(const uint2* tile, int count, int e
         P x[U][CH];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const float* xr = X + (int64_t)ed[u].x * ldx;
+            const float* xr = K::row(X, ed[u].x, ldx);
 #pragma unroll
             for (int ch = 0; ch < CH; ++ch) x[u][ch].load(xr + cols.off[ch]);
         }
@@ -189,7 +215,7 @@ __device__ __forceinline__ float row_factor(int norm, int n, int k)
 // Transposed stage 2 (backward pass): every staged entry (c, v) of the tile adds
 // v * dy to row c of the output with fp32 atomics; edge slot e of E walks
 // entries e, e+E, ...  Atomics return nothing, so they pipeline by themselves.
-template <int G, int CH, int VEC, bool ALIGNED>
+template <int G, int CH, int VEC, bool ALIGNED, bool WIDE>
 __device__ __forceinline__ void scatter_tile(const uint2* tile, int count, int e, int E, float* out,
                                              int64_t ldo, const LaneCols<G, CH, VEC, ALIGNED>& cols,
                                              const Pack<VEC, ALIGNED> (&dy)[CH])
@@ -197,7 +223,7 @@ __device__ __forceinline__ void scatter_tile(const uint2* tile, int count, int e
     for (int j = e; j < count; j += E) {
         const uint2 ed = tile[j];
         const float v = __uint_as_float(ed.y);
-        float* dst = out + (int64_t)ed.x * ldo;
+        float* dst = RowKey<ALIGNED, WIDE>::row(out, ed.x, ldo);
 #pragma unroll
         for (int ch = 0; ch < CH; ++ch) {
             if (cols.ok[ch]) {

@@ -224,6 +224,42 @@ def test_randomised_shapes(es):
             check_edges(d, W, mode, seed, int(rng.choice([0, 1, 4, -1])), what="edges " + what)
 
 
+@pytest.mark.parametrize("ld", [1 << 20, (1 << 20) + 1])
+def test_row_offsets_beyond_32_bits(es, ld):
+    """A dense matrix whose largest row offset does not fit 32 bits (5 000 rows at
+    a row stride of 2^20 floats: 21 GB, touched sparsely) takes the kernels that
+    multiply column ids by the stride in 64 bits; same products, forward, column-
+    partitioned and transposed."""
+    import torch
+    import oracle
+    from gpu_util import check_Y
+    n, F = 5000, 8
+    rowptr, colidx, vals, Xh = _random_graph(n, 12.0, seed=ld % 97, F=F)
+    dev = "cuda:0"
+    big = torch.empty(n * ld, dtype=torch.float32, device=dev)
+    X = big.as_strided((n, F), (ld, 1))
+    X.copy_(torch.from_numpy(Xh))
+    rp, ci, va = (torch.from_numpy(a).to(dev) for a in (rowptr, colidx, vals))
+    Y = torch.empty((n, F), dtype=torch.float32, device=dev)
+    ws = torch.empty(es.es_spmm_workspace_bytes(n) // 4, dtype=torch.int32, device=dev)
+    for mode, W, opts in (("full", 0, None), ("fastrand", 5, None), ("bucket", 5, dict(long_row_threshold=3)),
+                          ("full", 0, dict(column_partition=1)), ("fastrand", 5, dict(column_partition=1))):
+        Y.fill_(float("nan"))
+        es.es_spmm_ws(rp, ci, va, X, Y, W, mode, 3, "none", opts, ws)
+        torch.cuda.synchronize()
+        Yref, den = oracle.spmm(rowptr, colidx, vals, Xh, F, W, mode, 3)
+        check_Y(Y.cpu().numpy(), Yref, den, f"wide row offsets ld={ld} {mode} W={W} opts={opts}")
+    # transposed product: the OUTPUT has the wide stride
+    dY = torch.from_numpy(Xh).to(dev)
+    big.zero_()
+    es.es_spmm_backward(rp, ci, va, dY, X, 5, "fastrand", 3)
+    torch.cuda.synchronize()
+    ref, den = oracle.spmm_backward(rowptr, colidx, vals, Xh, F, 5, "fastrand", 3)
+    check_Y(X.cpu().numpy(), ref, den, f"wide row offsets ld={ld} backward")
+    del big, X
+    torch.cuda.empty_cache()
+
+
 def test_long_rows_span_several_tiles(es):
     """Rows far longer than one LDS tile (full mode and W above the tile),
     including lengths that are multiples of 577 where the multiplier changes."""
