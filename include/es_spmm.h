@@ -180,6 +180,57 @@ int es_spmm_materialize_transposed(const int32_t* rowptr, const int32_t* colidx,
                                    int32_t* out_idx, float* out_vals, void* stream);
 
 /*
+ * es_spmm_transpose_graph -- the transposed graph that es_spmm_backward_pull
+ * reads: A^T in CSR form, built ONCE per graph (it does not depend on W, mode or
+ * seed).  Row c of the result lists every stored entry (r, c) of A as the row r
+ * it came from, its entry number idx inside row r, the slot that reads it under
+ * Equation 2, and its value.
+ *   t_ptr  [N+1] int32, written: start of each row of A^T (t_ptr[N] = nnz)
+ *   t_end  [N]   int32, written: end of each row (= t_ptr[c+1]); the build
+ *          advances it entry by entry
+ *   t_row  [nnz] int32, written: the row r of A the entry belongs to
+ *   t_idx  [nnz] int32, written: its entry number inside that row, 0 .. n_r - 1
+ *   t_slot [nnz] int32, written: (idx * P^-1) mod n_r, the slot i for which
+ *          Equation 2, (i * P) mod n_r, gives idx (P: the row's multiplier)
+ *   t_vals [nnz] fp32, written (vals == NULL: ones)
+ *   t_pinv [N]   int32, written: P^-1 mod n_r per row (0 for rows of < 2 entries)
+ * The order of the entries inside a row of A^T is unspecified (atomic cursor).
+ */
+int es_spmm_transpose_graph(const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                            int64_t N, int64_t nnz, int32_t* t_ptr, int32_t* t_end, int32_t* t_row,
+                            int32_t* t_idx, int32_t* t_slot, float* t_vals, int32_t* t_pinv,
+                            void* stream);
+
+/*
+ * es_spmm_backward_pull -- the same dX = sample_W(A)^T * dY as es_spmm_backward,
+ * computed as a gather over the transposed graph instead of an atomic scatter
+ * (training is the use Section 6.2 points to; there the graph stays and the seed
+ * changes every iteration).  Row c of dX sums factor_r * a_rc * dY[r, :] over the
+ * stored entries (r, c) that es_spmm_norm(..., W, mode, seed, norm) keeps for row
+ * r; whether it keeps entry idx of a row of n entries follows from inverting
+ * the sampling rule of Section 4.4: always for ES_FULL or n <= W; idx < W for
+ * ES_BUCKET; for ES_FASTRAND the slot that reads the entry is
+ * ((idx - off) * P^-1) mod n = (t_slot - off * P^-1) mod n (Equation 2 solved
+ * for the slot), kept iff that slot is < W.  No atomics: every output row is
+ * written once, results are bit-reproducible.
+ *   rowptr            the ORIGINAL graph's row pointers [N+1]
+ *   t_ptr .. t_pinv   as written by es_spmm_transpose_graph for that graph (t_end
+ *                     is not needed)
+ *   t_rows            [2 * N] int32, 8-byte aligned, scratch: every call
+ *                     overwrites it with each row's (length, rotation) for this
+ *                     seed; calls that share it must be ordered (same stream)
+ *   dY  N rows of F fp32, row stride ldy (input); dX likewise, stride ldx (output,
+ *       fully overwritten); they must not overlap
+ *   nnz, W, mode, seed, norm as in es_spmm_backward.
+ */
+int es_spmm_backward_pull(const int32_t* rowptr, const int32_t* t_ptr, const int32_t* t_row,
+                          const int32_t* t_idx, const int32_t* t_slot, const float* t_vals,
+                          const int32_t* t_pinv, int32_t* t_rows,
+                          const float* dY, float* dX,
+                          int64_t N, int64_t nnz, int32_t F, int32_t ldy, int32_t ldx,
+                          int32_t W, int32_t mode, uint64_t seed, int32_t norm, void* stream);
+
+/*
  * es_spmm_validate_csr -- checks on the device what every other entry point
  * takes on trust (see "Not checked" above); meant to be run once on a graph of
  * unknown origin, since a bad column id makes es_spmm read outside X.

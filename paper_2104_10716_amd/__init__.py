@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     es_spmm,
     es_spmm_backward,
     es_spmm_backward_ex,
+    es_spmm_backward_pull,
     es_spmm_ex,
     es_launch_opts_t,
     es_spmm_launch_info,
@@ -25,6 +26,7 @@ from .binding import (  # noqa: F401
     es_spmm_sample_edges,
     es_spmm_status_string,
     es_spmm_tile_slots,
+    es_spmm_transpose_graph,
     es_spmm_validate_csr,
     es_spmm_static_ws,
     es_spmm_workspace_bytes,

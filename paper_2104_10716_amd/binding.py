@@ -86,6 +86,13 @@ def load_library():
     lib.es_spmm_materialize_transposed.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int64,
                                                    ctypes.c_int32, ctypes.c_int32, ctypes.c_uint64,
                                                    ctypes.c_int32, vp, vp, vp, vp, vp]
+    lib.es_spmm_transpose_graph.restype = ctypes.c_int
+    lib.es_spmm_transpose_graph.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp,
+                                            vp]
+    lib.es_spmm_backward_pull.restype = ctypes.c_int
+    lib.es_spmm_backward_pull.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64,
+                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                          ctypes.c_int32, ctypes.c_uint64, ctypes.c_int32, vp]
     lib.es_spmm_validate_csr.restype = ctypes.c_int
     lib.es_spmm_validate_csr.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int64, vp, vp]
     lib.es_spmm_launch_info.restype = ctypes.c_int
@@ -376,6 +383,63 @@ def es_spmm_materialize_transposed(rowptr, colidx, vals, W: int, mode, seed: int
     if rc != 0:
         raise EsSpmmError(rc, "es_spmm_materialize_transposed")
     return out_ptr, out_end, out_idx, out_vals
+
+
+def es_spmm_transpose_graph(rowptr, colidx, vals, stream=None):
+    """Transposed graph for es_spmm_backward_pull, built once per graph: a dict of device
+    tensors t_ptr [N+1], t_end [N], t_row, t_idx, t_slot, t_vals [nnz], t_pinv [N], plus
+    t_rows [2N], the per-call scratch of es_spmm_backward_pull."""
+    import torch
+    lib = load_library()
+    N = rowptr.numel() - 1
+    nnz = colidx.numel()
+    dev = rowptr.device
+    t = {"t_ptr": torch.empty((N + 1,), dtype=torch.int32, device=dev),
+         "t_end": torch.empty((N,), dtype=torch.int32, device=dev),
+         "t_row": torch.empty((nnz,), dtype=torch.int32, device=dev),
+         "t_idx": torch.empty((nnz,), dtype=torch.int32, device=dev),
+         "t_slot": torch.empty((nnz,), dtype=torch.int32, device=dev),
+         "t_rows": torch.empty((2 * N,), dtype=torch.int32, device=dev),
+         "t_vals": torch.empty((nnz,), dtype=torch.float32, device=dev),
+         "t_pinv": torch.empty((N,), dtype=torch.int32, device=dev)}
+    rc = lib.es_spmm_transpose_graph(
+        _dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(colidx, torch.int32, "colidx"),
+        _dev_ptr(vals, torch.float32, "vals"), N, nnz, t["t_ptr"].data_ptr() or None,
+        t["t_end"].data_ptr() or None, t["t_row"].data_ptr() or None, t["t_idx"].data_ptr() or None,
+        t["t_slot"].data_ptr() or None, t["t_vals"].data_ptr() or None, t["t_pinv"].data_ptr() or None,
+        _stream_ptr(stream))
+    if rc != 0:
+        raise EsSpmmError(rc, "es_spmm_transpose_graph")
+    return t
+
+
+def es_spmm_backward_pull(rowptr, t, dY, dX, W: int, mode, seed: int = 0, norm="none",
+                          F: Optional[int] = None, stream=None):
+    """dX[:, :F] = sample_W(A)^T @ dY[:, :F] as a gather over `t`, the dict
+    es_spmm_transpose_graph returned for the same graph; returns dX."""
+    import torch
+    lib = load_library()
+    if dY.dim() != 2 or dX.dim() != 2 or dY.stride(1) != 1 or dX.stride(1) != 1:
+        raise ValueError("dY and dX must be 2-D with contiguous columns")
+    N = rowptr.numel() - 1
+    if dY.shape[0] != N or dX.shape[0] != N:
+        raise ValueError("dY and dX need one row per CSR row")
+    if F is None:
+        F = dY.shape[1]
+    ldy = dY.stride(0) if N > 1 else max(dY.shape[1], 1)
+    ldx = dX.stride(0) if N > 1 else max(dX.shape[1], 1)
+    nm = NORMS[norm] if isinstance(norm, str) else int(norm)
+    rc = lib.es_spmm_backward_pull(
+        _dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(t["t_ptr"], torch.int32, "t_ptr"),
+        _dev_ptr(t["t_row"], torch.int32, "t_row"), _dev_ptr(t["t_idx"], torch.int32, "t_idx"),
+        _dev_ptr(t["t_slot"], torch.int32, "t_slot"), _dev_ptr(t["t_vals"], torch.float32, "t_vals"),
+        _dev_ptr(t["t_pinv"], torch.int32, "t_pinv"), _dev_ptr(t["t_rows"], torch.int32, "t_rows"),
+        _dev_ptr(dY, torch.float32, "dY"), _dev_ptr(dX, torch.float32, "dX"), N, t["t_row"].numel(),
+        int(F), int(ldy), int(ldx), int(W), _mode(mode), int(seed) & 0xFFFFFFFFFFFFFFFF, nm,
+        _stream_ptr(stream))
+    if rc != 0:
+        raise EsSpmmError(rc, "es_spmm_backward_pull")
+    return dX
 
 
 def es_spmm_validate_csr(rowptr, colidx, report=None, stream=None):

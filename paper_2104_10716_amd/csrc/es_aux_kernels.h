@@ -190,13 +190,15 @@ es_copy_int_kernel(const int32_t* __restrict__ in, int32_t* __restrict__ out, in
 
 // FILL == false: out_ptr[c + 1] += 1 per kept entry with column c.
 // FILL == true : the entry goes to position out_end[c]++ of out_idx / out_vals
-//                (value times the row factor).
+//                (value times the row factor) and, if asked for, out_pos (its
+//                position in the original CSR arrays).
 template <bool FILL>
 __global__ void __launch_bounds__(kBlockThreads)
 es_transpose_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
                     const float* __restrict__ vals, int64_t N, int32_t W, int32_t mode, uint64_t seed,
                     int32_t norm, int32_t logR, int32_t* out_ptr, int32_t* out_end,
-                    int32_t* __restrict__ out_idx, float* __restrict__ out_vals)
+                    int32_t* __restrict__ out_idx, float* __restrict__ out_vals,
+                    int32_t* __restrict__ out_pos)
 {
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
@@ -224,6 +226,7 @@ es_transpose_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restric
                 const int32_t pos = atomicAdd(out_end + c, 1);
                 out_idx[pos] = (int32_t)r;
                 out_vals[pos] = f * (vals ? vals[p] : 1.0f);
+                if (out_pos) out_pos[pos] = (int32_t)p;      // where the entry sits in the original CSR
             }
         });
     }

@@ -28,7 +28,7 @@ __device__ __forceinline__ void row_block(const Args& a, uint32_t vb, uint2* lds
     const int l = t & (G - 1);                   // column lane
     const int E = team >> LOG_G;                 // edge slots per row (>= 1)
     const int T = kTileSlots >> logR;            // tile slots per row
-    uint2* tile = lds + wave * kWaveTileStride + rs * (T + 1);
+    uint2* tile = lds + wave * kWaveTileStride + rs * (T + E);   // E pad slots: the rows' reads of slots j .. j+E-1 miss each other's banks
 
     const int64_t r = ((((int64_t)vb * kWavesPerBlock) + wave) << logR) + rs;
     const bool rvalid = r < a.N;

@@ -22,6 +22,20 @@ __device__ __forceinline__ uint64_t splitmix64_output(uint64_t seed, uint64_t co
     return z ^ (z >> 31);
 }
 
+// FastRand multiplier of a row of n entries: 577 (Equation 2), or the first of
+// the next primes that does not divide n, so that the picks stay distinct.
+__device__ __forceinline__ uint32_t fastrand_multiplier(uint32_t n)
+{
+    return (n % 577u) ? 577u : (n % 587u) ? 587u : (n % 593u) ? 593u : 599u;
+}
+
+// Per-row rotation of the FastRand picks: 0 for seed 0 (exactly Equation 2).
+__device__ __forceinline__ uint32_t fastrand_offset(uint64_t seed, int64_t row, uint32_t n)
+{
+    if (seed == 0) return 0u;
+    return (uint32_t)(splitmix64_output(seed, (uint64_t)row + 1u) >> 32) % n;
+}
+
 struct RowSampler {
     uint32_t idx;    // entry number the next call returns
     uint32_t step;   // increment per call, already reduced mod n
@@ -37,10 +51,8 @@ struct RowSampler {
             wrap = 0xFFFFFFFFu;
             return;
         }
-        const uint32_t P = (n % 577u) ? 577u : (n % 587u) ? 587u : (n % 593u) ? 593u : 599u;
-        uint32_t off = 0;
-        if (seed != 0)
-            off = (uint32_t)(splitmix64_output(seed, (uint64_t)row + 1u) >> 32) % n;
+        const uint32_t P = fastrand_multiplier(n);
+        const uint32_t off = fastrand_offset(seed, row, n);
         if (first < 65536u)
             idx = (off + (first * P) % n) % n;               // both terms < n < 2^31
         else

@@ -40,6 +40,7 @@
 #include "es_fused_kernel.h"
 #include "es_part_kernel.h"
 #include "es_aux_kernels.h"
+#include "es_pull_kernel.h"
 
 // Workspace of es_spmm_static_ws: the cuts array of the column-partitioned
 // product for up to ES_SPMM_STATIC_WS_MAX_ROWS rows, in static device memory.
@@ -425,6 +426,10 @@ int es_run(const int32_t* rowptr, const int32_t* colidx, const float* vals, cons
     return err == hipSuccess ? ES_OK : ES_ERR_LAUNCH;
 }
 
+int build_transposed(const int32_t* rowptr, const int32_t* colidx, const float* vals, int64_t N,
+                     int64_t nnz, int32_t W, int32_t mode, uint64_t seed, int32_t norm, int32_t* out_ptr,
+                     int32_t* out_end, int32_t* out_idx, float* out_vals, int32_t* out_pos, void* stream);
+
 }  // namespace
 
 extern "C" {
@@ -594,6 +599,106 @@ int es_spmm_materialize_transposed(const int32_t* rowptr, const int32_t* colidx,
                                    int32_t norm, int32_t* out_ptr, int32_t* out_end, int32_t* out_idx,
                                    float* out_vals, void* stream)
 {
+    return build_transposed(rowptr, colidx, vals, N, nnz, W, mode, seed, norm, out_ptr, out_end, out_idx,
+                            out_vals, nullptr, stream);
+}
+
+int es_spmm_transpose_graph(const int32_t* rowptr, const int32_t* colidx, const float* vals, int64_t N,
+                            int64_t nnz, int32_t* t_ptr, int32_t* t_end, int32_t* t_row, int32_t* t_idx,
+                            int32_t* t_slot, float* t_vals, int32_t* t_pinv, void* stream)
+{
+    if (N > 0 && (!t_idx || !t_slot || !t_pinv)) return ES_ERR_INVALID_ARG;
+    // t_idx first receives every entry's CSR position, then becomes its entry number
+    const int rc = build_transposed(rowptr, colidx, vals, N, nnz, 0, ES_FULL, 0, ES_NORM_NONE, t_ptr, t_end,
+                                    t_row, t_vals, t_idx, stream);
+    if (rc != ES_OK || N == 0) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t pb = (N + kBlockThreads - 1) / kBlockThreads;
+    if (pb > INT32_MAX) return ES_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(es_pinv_kernel, dim3((uint32_t)pb), dim3(kBlockThreads), 0, st, rowptr, N, t_pinv);
+    if (hipGetLastError() != hipSuccess) return ES_ERR_LAUNCH;
+    int64_t eb = (nnz + kBlockThreads - 1) / kBlockThreads;
+    if (eb > 65536) eb = 65536;
+    if (eb > 0) {
+        hipLaunchKernelGGL(es_pull_entries_kernel, dim3((uint32_t)eb), dim3(kBlockThreads), 0, st, rowptr,
+                           t_pinv, t_row, nnz, t_idx, t_slot);
+        if (hipGetLastError() != hipSuccess) return ES_ERR_LAUNCH;
+    }
+    return ES_OK;
+}
+
+int es_spmm_backward_pull(const int32_t* rowptr, const int32_t* t_ptr, const int32_t* t_row,
+                          const int32_t* t_idx, const int32_t* t_slot, const float* t_vals,
+                          const int32_t* t_pinv, int32_t* t_rows, const float* dY, float* dX, int64_t N,
+                          int64_t nnz, int32_t F, int32_t ldy, int32_t ldx, int32_t W, int32_t mode,
+                          uint64_t seed, int32_t norm, void* stream)
+{
+    const int bad = check_sizes(N, nnz, F, ldy, ldx, W, mode, norm);
+    if (bad != ES_OK) return bad;
+    if (N == 0) return ES_OK;
+    if (!rowptr || !t_ptr || !dY || !dX) return ES_ERR_INVALID_ARG;
+    if (!t_pinv || !t_rows || reinterpret_cast<uintptr_t>(t_rows) % 8) return ES_ERR_INVALID_ARG;
+    if (nnz > 0 && (!t_row || !t_idx || !t_slot || !t_vals)) return ES_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(dY) % 4 || reinterpret_cast<uintptr_t>(dX) % 4) return ES_ERR_INVALID_ARG;
+    const bool aligned = (F % 4 == 0) && (ldx % 4 == 0) && (ldy % 4 == 0) &&
+                         (reinterpret_cast<uintptr_t>(dY) % 16 == 0) &&
+                         (reinterpret_cast<uintptr_t>(dX) % 16 == 0);
+    const Shape s = pick_shape(F, aligned);
+    Args a;
+    a.rowptr = rowptr; a.colidx = nullptr; a.vals = nullptr; a.X = dY; a.Y = dX;
+    a.N = N; a.seed = seed; a.F = F; a.ldx = ldy; a.ldy = ldx;
+    a.W = (mode == ES_FULL) ? INT32_MAX : W;
+    a.mode = mode; a.logR = 0; a.norm = norm; a.long_k = INT32_MAX;
+    const int64_t nblocks = (N + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t per_xcd = (nblocks + kNumXcd - 1) / kNumXcd;
+    a.nblocks = (uint32_t)nblocks; a.blocks_per_xcd = (uint32_t)per_xcd; a.long_blocks = 0;
+    a.cuts = nullptr; a.part_cols = 0; a.phase = 0;
+    const int cols_per_block = s.G * s.CH * s.vec;
+    const int64_t grid_y = ((int64_t)F + cols_per_block - 1) / cols_per_block;
+    if (per_xcd * kNumXcd > INT32_MAX || grid_y > 65535) return ES_ERR_UNSUPPORTED;
+    const int64_t stride_units = s.aligned ? ldy / 4 : ldy;          // rows of dY are what gets gathered
+    const bool wide = (uint64_t)N * (uint64_t)stride_units > 0xFFFFFFFFull;
+    a.stride_units = wide ? 0u : (uint32_t)stride_units;
+    const dim3 grid((uint32_t)(per_xcd * kNumXcd), (uint32_t)grid_y);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // per-row (length, rotation) of this call
+    int2* rows = reinterpret_cast<int2*>(t_rows);
+    const int64_t rb = (N + kBlockThreads - 1) / kBlockThreads;
+    if (rb > INT32_MAX) return ES_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(es_pull_rows_kernel, dim3((uint32_t)rb), dim3(kBlockThreads), 0, st, rowptr, t_pinv, N,
+                       mode, seed, a.W, rows);
+    if (hipGetLastError() != hipSuccess) return ES_ERR_LAUNCH;
+    bool launched = false;
+#define ES_PULL(G_, CH_, V_, A_)                                                                     \
+    if (s.G == G_ && s.CH == CH_ && s.vec == V_ && s.aligned == A_) {                                \
+        if (wide)                                                                                    \
+            hipLaunchKernelGGL((es_pull_kernel<G_, CH_, V_, A_, true>), grid, dim3(kBlockThreads), 0, st, a,  \
+                               t_ptr, t_row, t_idx, t_slot, t_vals, rows);                                 \
+        else                                                                                         \
+            hipLaunchKernelGGL((es_pull_kernel<G_, CH_, V_, A_, false>), grid, dim3(kBlockThreads), 0, st, a, \
+                               t_ptr, t_row, t_idx, t_slot, t_vals, rows);                                 \
+        launched = true;                                                                             \
+    }
+    ES_PULL(4, 1, 4, true) ES_PULL(8, 1, 4, true) ES_PULL(16, 1, 4, true) ES_PULL(32, 1, 4, true)
+    ES_PULL(64, 1, 4, true) ES_PULL(64, 2, 4, true) ES_PULL(64, 4, 4, true)
+    ES_PULL(4, 1, 4, false) ES_PULL(8, 1, 4, false) ES_PULL(16, 1, 4, false) ES_PULL(32, 1, 4, false)
+    ES_PULL(64, 1, 4, false) ES_PULL(64, 2, 4, false) ES_PULL(64, 4, 4, false)
+    ES_PULL(4, 1, 1, false)
+#undef ES_PULL
+    if (!launched) return ES_ERR_UNSUPPORTED;
+    return hipGetLastError() == hipSuccess ? ES_OK : ES_ERR_LAUNCH;
+}
+
+}  // extern "C"
+
+namespace {
+
+// Transposed (sampled) graph: count the kept entries per column, scan, then
+// drop every entry into its column's segment through a per-column cursor.
+int build_transposed(const int32_t* rowptr, const int32_t* colidx, const float* vals, int64_t N,
+                     int64_t nnz, int32_t W, int32_t mode, uint64_t seed, int32_t norm, int32_t* out_ptr,
+                     int32_t* out_end, int32_t* out_idx, float* out_vals, int32_t* out_pos, void* stream)
+{
     if (N < 0 || nnz < 0 || nnz > INT32_MAX) return ES_ERR_INVALID_ARG;
     if (mode != ES_FULL && mode != ES_BUCKET && mode != ES_FASTRAND) return ES_ERR_INVALID_ARG;
     if (mode != ES_FULL && W < 1) return ES_ERR_INVALID_ARG;
@@ -619,7 +724,7 @@ int es_spmm_materialize_transposed(const int32_t* rowptr, const int32_t* colidx,
 
     hipLaunchKernelGGL(es_transpose_kernel<false>, dim3((uint32_t)nblocks), dim3(kBlockThreads), 0, st,
                        rowptr, colidx, vals, N, Wk, mode, seed, norm, logR, out_ptr, out_end, out_idx,
-                       out_vals);
+                       out_vals, out_pos);
     ES_CHECK_LAUNCH();
     hipLaunchKernelGGL(es_kept_scan_local_kernel, dim3((uint32_t)nscan), dim3(kBlockThreads), 0, st,
                        static_cast<const int32_t*>(nullptr), N, Wk, mode, out_ptr);
@@ -635,11 +740,15 @@ int es_spmm_materialize_transposed(const int32_t* rowptr, const int32_t* colidx,
     ES_CHECK_LAUNCH();
     hipLaunchKernelGGL(es_transpose_kernel<true>, dim3((uint32_t)nblocks), dim3(kBlockThreads), 0, st,
                        rowptr, colidx, vals, N, Wk, mode, seed, norm, logR, out_ptr, out_end, out_idx,
-                       out_vals);
+                       out_vals, out_pos);
     ES_CHECK_LAUNCH();
 #undef ES_CHECK_LAUNCH
     return ES_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 int es_spmm_validate_csr(const int32_t* rowptr, const int32_t* colidx, int64_t N, int64_t nnz,
                          int32_t* report, void* stream)

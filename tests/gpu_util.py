@@ -129,3 +129,17 @@ def check_backward_against_oracle(d, W, mode, seed=0, norm="none", what="", opts
     torch.cuda.synchronize()
     ref, den = oracle.spmm_backward(d.h_rowptr, d.h_colidx, d.h_vals, d.h_X, d.F, W, mode, seed, norm=norm)
     return check_Y(dX.cpu().numpy(), ref, den, what or f"backward {mode} W={W} seed={seed} norm={norm}")
+
+
+def check_backward_pull_against_oracle(d, t, W, mode, seed=0, norm="none", what=""):
+    """es_spmm_backward_pull on DeviceCSR `d` with its transposed graph `t`
+    (its X plays the upstream gradient dY) against the oracle's transposed
+    product, every element."""
+    import torch
+    import oracle
+    import paper_2104_10716_amd as es
+    dX = torch.full((d.N, d.F), float("nan"), dtype=torch.float32, device=d.X.device)
+    es.es_spmm_backward_pull(d.rowptr, t, d.X, dX, W, mode, seed, norm, F=d.F)
+    torch.cuda.synchronize()
+    ref, den = oracle.spmm_backward(d.h_rowptr, d.h_colidx, d.h_vals, d.h_X, d.F, W, mode, seed, norm=norm)
+    return check_Y(dX.cpu().numpy(), ref, den, what or f"backward pull {mode} W={W} seed={seed} norm={norm}")

@@ -408,6 +408,77 @@ def test_backward_small_graphs(es, F, ldx):
     check_backward_against_oracle(du, 4, "fastrand", 1, what=f"backward unit values F={F}")
 
 
+@pytest.mark.parametrize("F,ldx", [(3, 3), (16, 16), (41, 41), (64, 68), (100, 128), (256, 256), (520, 520)])
+def test_backward_pull_small_graphs(es, F, ldx):
+    """es_spmm_backward_pull (gather over the transposed graph, the sampling rule
+    inverted per stored entry) against the oracle's transposed product: every
+    mode, width, seed and row factor from ONE transposed graph."""
+    import torch
+    from gpu_util import DeviceCSR, check_backward_pull_against_oracle
+    rowptr, colidx, vals, dY = _random_graph(650, 12.0, seed=100 + F, F=F, ldx=ldx)
+    d = DeviceCSR(rowptr, colidx, vals, dY, F=F)
+    t = es.es_spmm_transpose_graph(d.rowptr, d.colidx, d.vals)
+    torch.cuda.synchronize()
+    assert int(t["t_ptr"][-1]) == colidx.size and torch.equal(t["t_end"], t["t_ptr"][1:])
+    maxdeg = int(np.diff(rowptr).max())
+    for mode, W in (("full", 0), ("bucket", 4), ("fastrand", 1), ("fastrand", 4), ("fastrand", maxdeg - 1),
+                    ("fastrand", maxdeg + 3)):
+        for seed in (0, 31, 2 ** 63 + 5):
+            for norm in ("none", "mean", "rescale"):
+                check_backward_pull_against_oracle(d, t, W, mode, seed, norm,
+                                                   what=f"pull F={F} {mode} W={W} seed={seed} {norm}")
+    du = DeviceCSR(rowptr, colidx, None, dY, F=F)              # unweighted: the structure holds ones
+    tu = es.es_spmm_transpose_graph(du.rowptr, du.colidx, None)
+    check_backward_pull_against_oracle(du, tu, 4, "fastrand", 1, what=f"pull unit values F={F}")
+
+
+def test_backward_pull_row_lengths_that_change_the_multiplier(es):
+    """Rows of 577, 1154, 577*587 and 2*577*587 entries (multipliers 587 and 593)
+    and rows spanning several tiles: the inverse of Equation 2 must pick exactly
+    the entries the forward sampler reads."""
+    from gpu_util import DeviceCSR, check_backward_pull_against_oracle
+    rng = np.random.default_rng(3)
+    N = 700_000
+    lengths = {0: 577, 5: 1154, 9: 577 * 587, 11: 2 * 577 * 587, 40: 5000, 41: 1, 42: 2, 43: 587, 44: 600}
+    lens = np.zeros(N, dtype=np.int64)
+    for r, L in lengths.items():
+        lens[r] = L
+    rowptr = np.zeros(N + 1, dtype=np.int32)
+    rowptr[1:] = np.cumsum(lens)
+    colidx = np.concatenate([np.sort(rng.choice(N, size=L, replace=False)) for L in lengths.values()]).astype(np.int32)
+    vals = rng.standard_normal(colidx.size).astype(np.float32)
+    dY = rng.uniform(-1, 1, (N, 4)).astype(np.float32)
+    d = DeviceCSR(rowptr, colidx, vals, dY)
+    t = es.es_spmm_transpose_graph(d.rowptr, d.colidx, d.vals)
+    for W in (1, 3, 64, 576, 1000, 70_000):
+        for seed in (0, 99):
+            check_backward_pull_against_oracle(d, t, W, "fastrand", seed, what=f"pull multipliers W={W} seed={seed}")
+    check_backward_pull_against_oracle(d, t, 64, "bucket", 0, what="pull multipliers bucket")
+
+
+def test_backward_pull_full_size(es):
+    """Configs 2 and 3 at full size, every element; pull and atomic scatter agree."""
+    import torch
+    from gpu_util import DeviceCSR, check_backward_pull_against_oracle
+    for cfg, cases in ((2, (("fastrand", 16), ("bucket", 128), ("full", 0))), (3, (("fastrand", 64), ("bucket", 16)))):
+        w = _workload(cfg)
+        dY = np.random.default_rng(cfg).standard_normal((w.N, w.F)).astype(np.float32)
+        d = DeviceCSR(w.rowptr, w.colidx, w.vals, dY)
+        t = es.es_spmm_transpose_graph(d.rowptr, d.colidx, d.vals)
+        for mode, W in cases:
+            worst = check_backward_pull_against_oracle(d, t, W, mode, 0, what=f"cfg{cfg} pull {mode} W={W}")
+            _say(f"cfg{cfg} backward pull {mode} W={W}: max normalised error {worst:.2e}")
+        a = torch.empty((w.N, w.F), dtype=torch.float32, device="cuda:0")
+        b = torch.empty_like(a)
+        es.es_spmm_backward_pull(d.rowptr, t, d.X, a, 32, "fastrand", 7, "mean")
+        es.es_spmm_backward_pull(d.rowptr, t, d.X, b, 32, "fastrand", 7, "mean")
+        assert torch.equal(a, b)                                  # no atomics: bit-reproducible
+        es.es_spmm_backward(d.rowptr, d.colidx, d.vals, d.X, b, 32, "fastrand", 7, "mean")
+        torch.cuda.synchronize()
+        assert torch.allclose(a, b, rtol=1e-3, atol=1e-4)
+        del d, t, a, b
+
+
 def test_backward_full_size(es):
     """Transposed product on configs 2 and 3 at full size, every element
     against the oracle; and the adjoint identity <A_s X, dY> = <X, A_s^T dY>
