@@ -20,6 +20,11 @@ workload, e.g. `--config 4` or `--config 5 --feature-width 41`):
 
 usage: python rocprof_summary.py DIR NAME KEY [ARGS...]
    NAME  file name under profiles/ (without .md);  KEY  entry of traffic.json ("config4", "config5:F41")
+
+Second form, for the legs that are not the W sweep (`bench.py --only backward|aux`): a per-kernel
+table (mean duration from the trace run, mean FETCH_SIZE / WRITE_SIZE / atomic counters per dispatch
+from the counter runs DIR/fetch, DIR/write, DIR/atomic):
+       python rocprof_summary.py --kernels DIR NAME "TITLE" [ARGS...]
 """
 from __future__ import annotations
 
@@ -83,7 +88,59 @@ def kernel_mean(rows, counter, needle, first=None, largest=None):
     return sum(v) / len(v) if v else None
 
 
+def by_kernel(rows, counter):
+    """{short kernel name: (mean counter value, mean dispatch ns under the counter run, dispatches)}"""
+    acc = collections.defaultdict(list)
+    for r in rows:
+        if r["Counter_Name"] == counter and "es_" in r["Kernel_Name"]:
+            acc[short(r["Kernel_Name"])].append((float(r["Counter_Value"]),
+                                                 int(r["End_Timestamp"]) - int(r["Start_Timestamp"])))
+    return {k: (sum(x for x, _ in v) / len(v), sum(t for _, t in v) / len(v), len(v)) for k, v in acc.items()}
+
+
+def kernels_main() -> int:
+    d, name, title = sys.argv[2], sys.argv[3], sys.argv[4]
+    bench_args = " ".join(sys.argv[5:])
+    import bench
+    out = [f"# rocprofv3 summary: {title}\n",
+           f"Kernel sources at hash `{bench.kernel_source_hash()}`. All commands run from the repository root on one "
+           f"MI355X (`cd /tmp && export TMPDIR=/tmp` first); `<args>` = `{bench_args}`.\n",
+           "`rocprofv3 --kernel-trace --stats -d <dir> -o t --output-format csv -- python3 bench.py <args>`; counters: "
+           "the same command after `rocprofv3 --pmc FETCH_SIZE`, `--pmc WRITE_SIZE` and `--pmc TCC_ATOMIC_sum "
+           "TCC_EA0_ATOMIC_sum` (one run each). FETCH_SIZE is scaled by 2.000, WRITE_SIZE by 1.000 (the 1 GiB copy "
+           "calibration of the sweep profiles).\n"]
+    stats = {short(r["Name"]): r for r in csv.DictReader(open(os.path.join(d, "trace", "t_kernel_stats.csv")))}
+    fetch = by_kernel(counter_rows(d, "fetch"), "FETCH_SIZE")
+    write = by_kernel(counter_rows(d, "write"), "WRITE_SIZE")
+    at = counter_rows(d, "atomic")
+    atom, ea = by_kernel(at, "TCC_ATOMIC_sum"), by_kernel(at, "TCC_EA0_ATOMIC_sum")
+    out.append("| kernel | calls | avg us | min us | max us | fetched MB | written MB | L2 atomic requests (M) | "
+               "atomics sent on to memory (M) | atomic requests / s (G) |\n|---|---|---|---|---|---|---|---|---|---|")
+    for k, r in stats.items():
+        if "es_" not in k:
+            continue
+        f = fetch.get(k, (0, 0, 0))[0] * 2.0 * KIB / 1e6
+        w = write.get(k, (0, 0, 0))[0] * KIB / 1e6
+        a_ = atom.get(k)
+        e_ = ea.get(k)
+        rate = "-" if not a_ or a_[0] == 0 else f"{a_[0] / a_[1]:.1f}"
+        out.append(f"| `{k}` | {r['Calls']} | {float(r['AverageNs']) / 1e3:.1f} | {int(r['MinNs']) / 1e3:.1f} | "
+                   f"{int(r['MaxNs']) / 1e3:.1f} | {f:.1f} | {w:.1f} | {'-' if not a_ else f'{a_[0] / 1e6:.2f}'} | "
+                   f"{'-' if not e_ else f'{e_[0] / 1e6:.2f}'} | {rate} |")
+    out.append("\nbench.py output of the trace run (stderr log lines):\n\n```")
+    err = os.path.join(d, "trace.err")
+    if os.path.exists(err):
+        out += [l.rstrip() for l in open(err) if l.startswith("  ")]
+    out.append("```\n")
+    with open(os.path.join(ROOT, "profiles", name + ".md"), "w") as fh:
+        fh.write("\n".join(out))
+    print("\n".join(out))
+    return 0
+
+
 def main() -> int:
+    if sys.argv[1] == "--kernels":
+        return kernels_main()
     d, name, key = sys.argv[1], sys.argv[2], sys.argv[3]
     bench_args = " ".join(sys.argv[4:])
     import bench
