@@ -71,6 +71,19 @@ def sector_adjusted_bytes(N: int, nnz_kept: int, nnz_kept_strided: int, F: int, 
             + 4 * F * nnz_kept + 4 * F * N)
 
 
+def line_floor_bytes(N: int, nnz_kept: int, F: int, ldx: int, L: int) -> int:
+    """B_eff with each gathered row of X counted as the whole L-byte lines it
+    touches: a row of 4F bytes starting at byte 4*ldx*c touches
+    ceil((start mod L + 4F) / L) lines; averaged over the start offsets that
+    occur (multiples of gcd(4*ldx, L)).  What a kernel moves at least when no
+    line is ever shared between two gathers."""
+    from math import gcd
+    step = gcd(4 * ldx, L)
+    offs = range(0, L, step)
+    lines = sum(-(-(o + 4 * F) // L) for o in offs) / len(offs)
+    return int(4 * (N + 1) + 8 * nnz_kept + lines * L * nnz_kept + 4 * F * N)
+
+
 def kernel_source_hash() -> str:
     """Hash of the kernel sources; profiles/traffic.json carries the hash it was measured at."""
     h = hashlib.sha256()
@@ -198,6 +211,12 @@ def rates_row(dw, mode, W, ms, traffic_calls, L):
     if L:
         B_sec = sector_adjusted_bytes(dw.N, kept, dw.nnz_kept_strided(mode, W), dw.F, L)
         row["eff_sector_adjusted_GBps"] = round(B_sec / (ms * 1e6), 1)
+        ldx = int(dw.X.stride(0))
+        if (4 * ldx) % L or (4 * dw.F) % L:                    # rows do not tile whole lines (F = 41, 64, ...)
+            B_line = line_floor_bytes(dw.N, kept, dw.F, ldx, L)
+            row["line_floor_bytes"] = B_line
+            row["line_floor_over_B_eff"] = round(B_line / B_eff, 3)
+            row["line_floor_GBps"] = round(B_line / (ms * 1e6), 1)
     t = traffic_calls.get(call_label(mode, W))
     if t:
         tb = t["fetch_bytes"] + t["write_bytes"]
@@ -265,16 +284,18 @@ def cpu_baseline(dw, calls, target_seconds=12.0, max_passes=6):
 
     def sized(threads):
         oracle.set_threads(threads)
-        probe = np.sort(order[:max(1, dw.N // 200)])
-        _, dt = run(probe)                                        # 0.5 % of the rows sizes the sample
-        frac = min(1.0, target_seconds / max(dt, 1e-3) / 200.0)
+        probe = np.sort(order[:max(1, dw.N // 100)])
+        run(probe[: max(1, probe.size // 10)])                    # first touch: threads, page cache
+        _, dt = run(probe)                                        # 1 % of the rows sizes the sample
+        frac = min(1.0, target_seconds / max(dt, 1e-3) / 100.0)
         rows = np.sort(order[:max(1, int(dw.N * frac))])
-        passes = 1 if frac < 1.0 else int(min(max_passes, max(1, target_seconds / max(dt * 200.0, 1e-3))))
         total = dt_sum = 0.0
-        for _ in range(passes):
+        passes = 0
+        while passes < max_passes and (passes == 0 or (frac >= 1.0 and dt_sum < target_seconds)):
             b, dt = run(rows)
             total += b
             dt_sum += dt
+            passes += 1
         return total / dt_sum / 1e9, dt_sum, rows.size, passes
 
     v, dt, nrows, passes = sized(cores)
@@ -642,8 +663,8 @@ def unweighted_norm_table(dw, dev):
     Y2 = torch.empty_like(dw.Y)
     for mode, W in (("fastrand", 16), ("fastrand", 64), ("bucket", 64), ("full", 0)):
         t_vals = _time_fn(lambda: dw.launch(mode, W))
-        t_norm = _time_fn(lambda: es.es_spmm_norm(dw.rowptr, dw.colidx, None, dw.X, Y2, W, mode, 0,
-                                                  "inv_degree", F=dw.F))
+        t_norm = _time_fn(lambda: es.es_spmm_ws(dw.rowptr, dw.colidx, None, dw.X, Y2, W, mode, 0,
+                                                "inv_degree", None, dw.ws, F=dw.F))
         dw.launch(mode, W)
         torch.cuda.synchronize()
         err = float((dw.Y - Y2).abs().max() / dw.Y.abs().max())

@@ -875,18 +875,24 @@ def test_config2_citation_like_full_size(es):
 
 
 def _cfg3_device():
+    """Config 3 on the device, calls routed through es_spmm_ws as in bench.py (the
+    exact product then runs column-partitioned)."""
     from gpu_util import DeviceCSR
     w = _workload(3)
-    return w, DeviceCSR(w.rowptr, w.colidx, w.vals, w.X)
+    return w, DeviceCSR(w.rowptr, w.colidx, w.vals, w.X).with_workspace()
 
 
 def test_config3_social_like_full_product(es):
     """Config 3 (113 M entries, rows up to 20 k): EVERY element of the exact
-    product against the oracle, in row blocks."""
+    product against the oracle, in row blocks -- through es_spmm_ws (column-
+    partitioned) and through plain es_spmm (rows up to 20 k on the long-row path)."""
     from gpu_util import check_every_element
     w, d = _cfg3_device()
     worst = check_every_element(d, 0, "full", what="cfg3 full")
-    _say(f"cfg3 full: max normalised error {worst:.2e} over all {w.N} x {w.F} elements")
+    _say(f"cfg3 full (es_spmm_ws): max normalised error {worst:.2e} over all {w.N} x {w.F} elements")
+    d.default_ws = None
+    worst = check_every_element(d, 0, "full", what="cfg3 full, no workspace")
+    _say(f"cfg3 full (es_spmm): max normalised error {worst:.2e} over all {w.N} x {w.F} elements")
 
 
 @pytest.mark.parametrize("mode", ["bucket", "fastrand"])
@@ -1055,7 +1061,8 @@ def test_config5_first_stage_F256(es):
     the oracle for W = 64 (both strategies) and the exact product."""
     from gpu_util import DeviceCSR, check_every_element
     g, Z1, _ = _gcn_first_stage_input()
-    d = DeviceCSR(g.rowptr, g.colidx, g.vals, Z1)
+    d = DeviceCSR(g.rowptr, g.colidx, g.vals, Z1).with_workspace()
+    assert es.es_spmm_launch_info(g.N, g.nnz, 256, 0, "full")["column_ranges"] == 8
     for mode, W in (("bucket", 64), ("fastrand", 64), ("full", 0)):
         worst = check_every_element(d, W, mode, 0, what=f"cfg5 F=256 {mode}")
         _say(f"cfg5 F=256 {mode} W={W}: max normalised error {worst:.2e} over all {g.N} x 256 elements")
@@ -1071,16 +1078,19 @@ def test_config5_second_stage_F41(es):
     H1, _ = oracle.spmm(g.rowptr, g.colidx, g.vals, Z1, 256, 64, "fastrand", 0, want_denom=False)
     Z2 = (np.maximum(H1, 0.0).astype(np.float32) @ W2).astype(np.float32)   # [N x 41]
     del H1, Z1
-    d = DeviceCSR(g.rowptr, g.colidx, g.vals, Z2)
+    d = DeviceCSR(g.rowptr, g.colidx, g.vals, Z2).with_workspace()
     for mode, W in (("bucket", 64), ("fastrand", 64), ("full", 0)):
         worst = check_every_element(d, W, mode, 0, what=f"cfg5 F=41 {mode}")
+    # and the exact product without a workspace (the unpartitioned kernel on 164-byte rows)
+    d.default_ws = None
+    worst = check_every_element(d, 0, "full", 0, what="cfg5 F=41 full, no workspace")
         _say(f"cfg5 F=41 {mode} W={W}: max normalised error {worst:.2e} over all {g.N} x 41 elements")
 
 
 def _cfg4_device():
     from gpu_util import DeviceCSR
     w = _workload(4)
-    return w, DeviceCSR(w.rowptr, w.colidx, w.vals, w.X)
+    return w, DeviceCSR(w.rowptr, w.colidx, w.vals, w.X).with_workspace()
 
 
 def test_config4_copurchase_like_full_product(es):
