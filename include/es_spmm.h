@@ -278,6 +278,13 @@ typedef struct {
                                     product whenever it applies (a workspace is given,
                                     mode is not ES_BUCKET, N >= 512), -1 = never, 0 =
                                     the library decides from N, F, W and nnz / N      */
+    int32_t kernel;              /* 1 = the row kernel (a row, or a row per team of
+                                    lanes, on a wave at a time); 2 = the flattened
+                                    kernel (a wave lays 256 / lanes_per_row rows end
+                                    to end and deals their entries to its edge slots:
+                                    for short rows); falls back to 1 where 2 does not
+                                    apply (F < 4, the backward pass, FastRand in the
+                                    column-partitioned product)                       */
 } es_launch_opts_t;
 
 /*
@@ -373,6 +380,8 @@ typedef struct {
     int32_t long_row_threshold;  /* rows keeping more entries are split             */
     int64_t long_row_workgroups; /* leading workgroups that serve such rows (or 0)  */
     int64_t grid_x, grid_y;      /* launch grid, 256 threads per workgroup          */
+    int32_t flattened;           /* 1: the flattened kernel would run (rows_per_wave then
+                                    is the number of rows a wave lays end to end)     */
     int32_t column_ranges;       /* 8: es_spmm_ws with a sufficient workspace would run
                                     the column-partitioned product (grid_x then is the
                                     grid of each of its 8 launches); 1: it would not  */

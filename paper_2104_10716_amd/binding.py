@@ -15,7 +15,8 @@ NORMS = {"none": ES_NORM_NONE, "mean": ES_NORM_MEAN, "rsqrt": ES_NORM_RSQRT, "re
 
 class es_launch_opts_t(ctypes.Structure):
     _fields_ = [("rows_per_wave", ctypes.c_int32), ("lanes_per_row", ctypes.c_int32),
-                ("long_row_threshold", ctypes.c_int32), ("column_partition", ctypes.c_int32)]
+                ("long_row_threshold", ctypes.c_int32), ("column_partition", ctypes.c_int32),
+                ("kernel", ctypes.c_int32)]
 
 
 class es_launch_info_t(ctypes.Structure):
@@ -24,7 +25,8 @@ class es_launch_info_t(ctypes.Structure):
                 ("rows_per_wave", ctypes.c_int32), ("edge_slots", ctypes.c_int32),
                 ("loads_in_flight", ctypes.c_int32), ("tile_slots_per_row", ctypes.c_int32),
                 ("long_row_threshold", ctypes.c_int32), ("long_row_workgroups", ctypes.c_int64),
-                ("grid_x", ctypes.c_int64), ("grid_y", ctypes.c_int64), ("column_ranges", ctypes.c_int32)]
+                ("grid_x", ctypes.c_int64), ("grid_y", ctypes.c_int64), ("flattened", ctypes.c_int32),
+                ("column_ranges", ctypes.c_int32)]
 
 
 _PKG = os.path.dirname(os.path.abspath(__file__))

@@ -39,6 +39,7 @@
 #include "es_tile.h"
 #include "es_fused_kernel.h"
 #include "es_part_kernel.h"
+#include "es_flat_kernel.h"
 #include "es_aux_kernels.h"
 #include "es_pull_kernel.h"
 
@@ -131,6 +132,35 @@ hipError_t launch_forward(const Args& a, dim3 grid, hipStream_t st)
     return hipGetLastError();
 }
 
+template <int G, bool ALIGNED, bool WIDE>
+hipError_t launch_flat(Args a, dim3 grid, bool partition, int32_t* cuts, hipStream_t st)
+{
+    if (!partition) {
+        if (a.long_blocks > 0) {
+            const uint32_t zb = (uint32_t)((a.N + kBlockThreads - 1) / kBlockThreads);
+            hipLaunchKernelGGL(es_zero_long_rows_kernel, dim3(zb), dim3(kBlockThreads), 0, st, a);
+            const hipError_t err = hipGetLastError();
+            if (err != hipSuccess) return err;
+        }
+        hipLaunchKernelGGL((es_spmm_flat_kernel<G, ALIGNED, WIDE>), grid, dim3(kBlockThreads), 0, st, a);
+        return hipGetLastError();
+    }
+    a.cuts = cuts;
+    a.part_cols = (int32_t)((a.N + kParts - 1) / kParts);
+    const uint32_t cb = (uint32_t)((a.N * kParts + kBlockThreads - 1) / kBlockThreads);
+    hipLaunchKernelGGL(es_cuts_kernel, dim3(cb), dim3(kBlockThreads), 0, st, a.rowptr, a.colidx, a.N,
+                       a.part_cols, cuts);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    for (int phase = 0; phase < kParts; ++phase) {
+        a.phase = phase;
+        hipLaunchKernelGGL((es_spmm_part_flat_kernel<G, ALIGNED, WIDE>), grid, dim3(kBlockThreads), 0, st, a);
+        err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
+    return hipSuccess;
+}
+
 // The transposed product always runs the 32-bit interleaved column mapping
 // (lane l owns columns l, l+G, ...): one atomic instruction then covers G
 // consecutive floats of an output row instead of every fourth one, which is
@@ -168,6 +198,7 @@ struct Overrides {
     int G = 0;                 // lanes_per_row cap, 0 = heuristic, -1 = never slice
     int32_t long_k = 0;        // long-row threshold, 0 = heuristic
     int partition = 0;         // column-partitioned product: 0 = heuristic, 1 = on, -1 = off
+    int kernel = 0;            // 0 = heuristic, 1 = row kernel, 2 = flattened kernel
 };
 
 int parse_opts(const es_launch_opts_t* opts, Overrides* ov)
@@ -176,6 +207,8 @@ int parse_opts(const es_launch_opts_t* opts, Overrides* ov)
     if (!opts) return ES_OK;
     if (opts->column_partition < -1 || opts->column_partition > 1) return ES_ERR_INVALID_ARG;
     ov->partition = opts->column_partition;
+    if (opts->kernel < 0 || opts->kernel > 2) return ES_ERR_INVALID_ARG;
+    ov->kernel = opts->kernel;
     const int32_t rpw = opts->rows_per_wave;
     if (rpw != 0) {
         if (rpw < 1 || rpw > 64 || (rpw & (rpw - 1))) return ES_ERR_INVALID_ARG;
@@ -215,6 +248,7 @@ struct Plan {
     int64_t grid_x, grid_y;    // launch grid (long-row workgroups included in grid_x)
     int64_t long_blocks;       // leading long-row workgroups
     bool partition;            // column-partitioned product (kParts phases, needs a workspace)
+    bool flat;                 // flattened kernel (es_flat_kernel.h) instead of the row kernel
 };
 
 int check_sizes(int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t ldy, int32_t W, int32_t mode,
@@ -253,6 +287,19 @@ bool pick_partition(int64_t N, double mean_kept, int32_t mode, int cols_per_bloc
     if (mean_kept < 128.0) return false;
     const double share = (double)N * cols_per_block * 4.0 / kParts;
     return share >= 1.0e6 && share <= 12.0e6;
+}
+
+// Whether to run the flattened kernel.  It takes the per-row instructions and
+// the lanes idled by unequal row lengths out, which pays while a row (or its
+// piece of a column range) keeps at most a few batches of entries; long rows
+// amortise all of that by themselves and the row kernel's long-row split suits
+// them better.
+bool pick_flat(double mean_kept, bool partition, int force)
+{
+    if (force == 1) return false;
+    if (force == 2) return true;
+    (void)mean_kept; (void)partition;
+    return false;
 }
 
 int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool aligned, bool backward,
@@ -296,6 +343,11 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
         s.G = slice_G;                                     // narrower column blocks, more of them
         s.CH = 1;
     }
+    // Flattened kernel: applies to 128-bit accesses; its row accumulators hold one
+    // column block of at most 256 columns, so wider rows are sliced to that.
+    const bool flat_applies = !backward && s.vec == 4 && !(p->partition && mode == ES_FASTRAND);
+    p->flat = flat_applies && pick_flat(mean, p->partition, ov.kernel);
+    if (p->flat) s.CH = 1;
     p->s = s;
 
     int logR = pick_logR(s, mean);
@@ -308,6 +360,11 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
     }
     p->logR = logR;
 
+    if (p->flat) {                                         // a wave lays 256 / G rows end to end
+        logR = 0;
+        while ((1 << logR) < 256 / s.G) ++logR;
+        p->logR = logR;
+    }
     const int64_t rows_per_block = (int64_t)kWavesPerBlock << logR;
     p->nblocks = (N + rows_per_block - 1) / rows_per_block;
     p->per_xcd = (p->nblocks + kNumXcd - 1) / kNumXcd;
@@ -326,7 +383,11 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
     const bool may_be_long = mode == ES_FULL || W > p->long_k;
     p->long_blocks = may_be_long ? ((N + kLongScanRows - 1) / kLongScanRows) * kLongSplit : 0;
     p->grid_x = p->per_xcd * kNumXcd + p->long_blocks;
-    if (p->partition) {
+    if (p->partition && p->flat) {                         // one sweep per launch, no long-piece handling
+        p->long_k = INT32_MAX;
+        p->long_blocks = 0;
+        p->grid_x = p->per_xcd * kNumXcd;
+    } else if (p->partition) {
         // a wave serves kPartGroups consecutive rows, one at a time; every launch
         // sweeps the rows twice, pieces above long_k first (es_part_kernel.h)
         p->logR = 0;
@@ -409,7 +470,7 @@ int es_run(const int32_t* rowptr, const int32_t* colidx, const float* vals, cons
     (p.partition ? launch_partitioned<G_, CH_, V_, A_, W_>(a, grid, static_cast<int32_t*>(workspace), st) \
                  : launch_forward<G_, CH_, V_, A_, W_>(a, grid, st))
 #define ES_CASE(G_, CH_, V_, A_)                                                          \
-    if (!backward && s.G == G_ && s.CH == CH_ && s.vec == V_ && s.aligned == A_)          \
+    if (!backward && !p.flat && s.G == G_ && s.CH == CH_ && s.vec == V_ && s.aligned == A_) \
         err = wide ? ES_LAUNCH(G_, CH_, V_, A_, true) : ES_LAUNCH(G_, CH_, V_, A_, false);
     ES_CASE(4, 1, 4, true) ES_CASE(8, 1, 4, true) ES_CASE(16, 1, 4, true) ES_CASE(32, 1, 4, true)
     ES_CASE(64, 1, 4, true) ES_CASE(64, 2, 4, true) ES_CASE(64, 4, 4, true)
@@ -420,6 +481,13 @@ int es_run(const int32_t* rowptr, const int32_t* colidx, const float* vals, cons
     if (backward && s.G == G_ && s.CH == CH_)   \
         err = wide ? launch_backward<G_, CH_, true>(a, grid, st) : launch_backward<G_, CH_, false>(a, grid, st);
     ES_BWD(4, 1) ES_BWD(8, 1) ES_BWD(16, 1) ES_BWD(32, 1) ES_BWD(64, 1) ES_BWD(64, 2) ES_BWD(64, 4)
+#define ES_FLAT(G_, A_)                                                                         \
+    if (p.flat && s.G == G_ && s.aligned == A_)                                                 \
+        err = wide ? launch_flat<G_, A_, true>(a, grid, p.partition, static_cast<int32_t*>(workspace), st)  \
+                   : launch_flat<G_, A_, false>(a, grid, p.partition, static_cast<int32_t*>(workspace), st);
+    ES_FLAT(4, true) ES_FLAT(8, true) ES_FLAT(16, true) ES_FLAT(32, true) ES_FLAT(64, true)
+    ES_FLAT(4, false) ES_FLAT(8, false) ES_FLAT(16, false) ES_FLAT(32, false) ES_FLAT(64, false)
+#undef ES_FLAT
 #undef ES_BWD
 #undef ES_CASE
 #undef ES_LAUNCH
@@ -549,13 +617,14 @@ int es_spmm_launch_info(int64_t N, int64_t nnz, int32_t F, int32_t ldx, int32_t 
     info->lanes_per_row = p.s.G;
     info->chunks_per_lane = p.s.CH;
     info->rows_per_wave = 1 << p.logR;
-    info->edge_slots = (64 >> p.logR) / p.s.G;
+    info->edge_slots = p.flat ? 64 / p.s.G : (64 >> p.logR) / p.s.G;
     info->loads_in_flight = 8 / p.s.CH;
     info->tile_slots_per_row = kTileSlots >> p.logR;
     info->long_row_threshold = p.long_k;
     info->long_row_workgroups = p.long_blocks;
     info->grid_x = p.grid_x;
     info->grid_y = p.grid_y;
+    info->flattened = p.flat ? 1 : 0;
     info->column_ranges = p.partition ? kParts : 1;
     return ES_OK;
 }

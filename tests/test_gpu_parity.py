@@ -61,6 +61,18 @@ def test_small_graph_all_modes(es, F, ldx):
                 for seed in (0, 12345):
                     check_against_oracle(d, W, mode, seed, ldy=ldx + 4 if F % 4 == 0 else None,
                                          what=f"{mode} F={F} W={W} seed={seed} rpw={rpw}", opts=opts)
+    # the flattened kernel (needs 128-bit accesses: F >= 4), whole and sliced, with and without long rows
+    if F >= 4:
+        for opts in (dict(kernel=2), dict(kernel=2, lanes_per_row=4), dict(kernel=2, long_row_threshold=5)):
+            info = es.es_spmm_launch_info(n, colidx.size, F, 3, "fastrand", ldx=ldx, ldy=ldx, opts=opts,
+                                          aligned16=(F % 4 == 0 and ldx % 4 == 0))
+            assert info["flattened"] == 1
+            check_against_oracle(d, 0, "full", what=f"flattened full F={F} {opts}", opts=opts)
+            for mode in ("bucket", "fastrand"):
+                for W in (1, 3, 8, maxdeg, maxdeg + 5):
+                    for seed in (0, 12345):
+                        check_against_oracle(d, W, mode, seed, ldy=ldx + 4 if F % 4 == 0 else None, norm="rescale",
+                                             what=f"flattened {mode} F={F} W={W} seed={seed} {opts}", opts=opts)
     # force the long-row path (segments + atomic adds) onto ordinary rows
     for thr in (1, 7):
         opts = dict(long_row_threshold=thr)
@@ -102,12 +114,15 @@ def test_column_partitioned_product(es, F, ldx):
     maxdeg = int(np.diff(rowptr).max())
     _say(f"column-partitioned F={F} ldx={ldx} maxdeg={maxdeg}")
     for rpw in (0, 1, 4, 64):
-        for lanes, thr in ((0, 0), (8, 0), (0, 2), (0, 10 ** 6)):      # thr: pieces above it go to the first sweep
+        for lanes, thr, kern in ((0, 0, 1), (8, 0, 1), (0, 2, 1), (0, 10 ** 6, 1), (0, 0, 2), (8, 0, 2), (4, 0, 2)):
+            if kern == 2 and (F < 4 or rpw):                          # thr: pieces above it go to the first sweep
+                continue
             opts = dict(workspace=True, column_partition=1, rows_per_wave=rpw, lanes_per_row=lanes,
-                        long_row_threshold=thr)
+                        long_row_threshold=thr, kernel=kern)
             info = es.es_spmm_launch_info(n, colidx.size, F, 8, "fastrand", ldx=ldx, ldy=ldx + 4,
                                           opts={k: v for k, v in opts.items() if k != "workspace"})
-            assert info["column_ranges"] == 8 and info["long_row_workgroups"] * 2 == info["grid_x"]
+            assert info["column_ranges"] == 8
+            assert info["long_row_workgroups"] * 2 == info["grid_x"] or info["flattened"]
             check_against_oracle(d, 0, "full", what=f"partitioned full F={F} rpw={rpw} lanes={lanes}", opts=opts)
             for W in (1, 7, 30, maxdeg - 1, maxdeg + 5):
                 for seed in (0, 12345):
@@ -209,11 +224,11 @@ def test_randomised_shapes(es):
         rpw = int(rng.choice([0, 0, 1, 2, 16, 64]))
         thr = int(rng.choice([0, 0, 1, 3, 40]))
         lanes = int(rng.choice([0, 0, 0, 4, 16]))
-        opts = dict(rows_per_wave=rpw, long_row_threshold=thr, lanes_per_row=lanes)
+        opts = dict(rows_per_wave=rpw, long_row_threshold=thr, lanes_per_row=lanes, kernel=int(rng.choice([0, 1, 2])))
         part = int(rng.choice([0, 0, 1, -1]))
         if part:
             opts.update(workspace=True, column_partition=part)
-        what = (f"case {case}: part={part} n={n} avg={avg} F={F} ld={F + pad} {mode} W={W} seed={seed} norm={norm} "
+        what = (f"case {case}: part={part} kernel={opts['kernel']} n={n} avg={avg} F={F} ld={F + pad} {mode} W={W} seed={seed} norm={norm} "
                 f"rpw={rpw} thr={thr} lanes={lanes}")
         _say(what)
         ldy = F + int(rng.choice([0, 0, 2, 4]))
@@ -286,6 +301,11 @@ def test_long_rows_span_several_tiles(es):
             for W in (16, 512, 576, 600, 1153, 3000):
                 for mode in ("bucket", "fastrand"):
                     check_against_oracle(d, W, mode, 77, what=f"long {mode} F={F} W={W} rpw={rpw}", opts=opts)
+        for opts in (dict(kernel=2), dict(kernel=2, long_row_threshold=600), dict(kernel=2, lanes_per_row=4)):
+            check_against_oracle(d, 0, "full", what=f"long full F={F} {opts}", opts=opts)
+            for W in (16, 512, 576, 600, 1153, 3000):
+                for mode in ("bucket", "fastrand"):
+                    check_against_oracle(d, W, mode, 77, what=f"long {mode} F={F} W={W} {opts}", opts=opts)
         for thr in (100, 512, 1000, 5000):  # move the long-row threshold around
             opts = dict(long_row_threshold=thr)
             check_against_oracle(d, 0, "full", what=f"long full F={F} threshold {thr}", opts=opts)
@@ -905,6 +925,25 @@ def test_config3_social_like_every_width(es, mode):
         _say(f"cfg3 {mode} W={W}: max normalised error {worst:.2e} over all {w.N} x {w.F} elements")
 
 
+@pytest.mark.parametrize("cfg", [2, 3, 4])
+def test_flattened_kernel_full_size(es, cfg):
+    """The flattened kernel forced on at full size: every element of Y against the
+    oracle for the smallest and largest W of the sweep and the exact product
+    (config 3: column-partitioned as well)."""
+    from gpu_util import DeviceCSR, check_every_element
+    w = _workload(cfg)
+    d = DeviceCSR(w.rowptr, w.colidx, w.vals, w.X).with_workspace()
+    cases = [("bucket", w.Ws[0]), ("fastrand", w.Ws[0]), ("fastrand", w.Ws[-1]), ("full", 0)]
+    for mode, W in cases:
+        opts = dict(workspace=d.default_ws, kernel=2)
+        worst = check_every_element(d, W, mode, 0, what=f"cfg{cfg} flattened {mode} W={W}", opts=opts)
+        _say(f"cfg{cfg} flattened {mode} W={W}: max normalised error {worst:.2e}")
+    if cfg == 3:
+        worst = check_every_element(d, 0, "full", what="cfg3 flattened, not partitioned",
+                                    opts=dict(workspace=d.default_ws, kernel=2, column_partition=-1))
+        _say(f"cfg3 flattened exact product without column ranges: max normalised error {worst:.2e}")
+
+
 def test_config3_column_partitioned(es):
     """Config 3 through es_spmm_ws (the library itself chooses the column-
     partitioned product here): every element against the oracle, and the result
@@ -1081,10 +1120,11 @@ def test_config5_second_stage_F41(es):
     d = DeviceCSR(g.rowptr, g.colidx, g.vals, Z2).with_workspace()
     for mode, W in (("bucket", 64), ("fastrand", 64), ("full", 0)):
         worst = check_every_element(d, W, mode, 0, what=f"cfg5 F=41 {mode}")
+        _say(f"cfg5 F=41 {mode} W={W}: max normalised error {worst:.2e} over all {g.N} x 41 elements")
     # and the exact product without a workspace (the unpartitioned kernel on 164-byte rows)
     d.default_ws = None
     worst = check_every_element(d, 0, "full", 0, what="cfg5 F=41 full, no workspace")
-        _say(f"cfg5 F=41 {mode} W={W}: max normalised error {worst:.2e} over all {g.N} x 41 elements")
+    _say(f"cfg5 F=41 full without a workspace: max normalised error {worst:.2e}")
 
 
 def _cfg4_device():

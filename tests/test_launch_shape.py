@@ -16,14 +16,17 @@ def _check(info, N, F, backward):
     G, CH, V = info["lanes_per_row"], info["chunks_per_lane"], info["vector_width"]
     R, E = info["rows_per_wave"], info["edge_slots"]
     assert V in (1, 4) and CH in (1, 2, 4) and G in (4, 8, 16, 32, 64)
-    assert R * G * E == 64 and E >= 1                     # a wave is R rows x E slots x G lanes
+    if info["flattened"]:
+        assert R * G == 256 and E * G == 64               # a wave lays 4E rows end to end for its E slots
+    else:
+        assert R * G * E == 64 and E >= 1                 # a wave is R rows x E slots x G lanes
     assert info["loads_in_flight"] * CH == 8
     assert info["tile_slots_per_row"] * R == es.es_spmm_tile_slots(1)
     assert G * CH * V * info["grid_y"] >= F               # every column is covered ...
     assert G * CH * V * (info["grid_y"] - 1) < F          # ... by no more column blocks than needed
     rows_per_workgroup = 4 * R
     row_groups = info["grid_x"] - info["long_row_workgroups"]
-    if info["column_ranges"] == 8:                        # a wave serves 4 row groups; two sweeps per launch
+    if info["column_ranges"] == 8 and not info["flattened"]:   # a wave serves 4 rows; two sweeps per launch
         rows_per_workgroup *= 4
         assert info["long_row_workgroups"] == row_groups
     assert row_groups % 8 == 0                            # one equal share per XCD
@@ -56,7 +59,7 @@ def test_long_rows_are_only_possible_when_the_long_part_is_launched():
         assert full["column_ranges"] == 1
         auto = es.es_spmm_launch_info(N, nnz, F, 0, "full")
         # the column-partitioned product sweeps its rows twice per launch (long pieces first)
-        if auto["column_ranges"] == 8:
+        if auto["column_ranges"] == 8 and not auto["flattened"]:
             assert auto["long_row_workgroups"] * 2 == auto["grid_x"]
         for W in (1, 16, 128, 512):
             s = es.es_spmm_launch_info(N, nnz, F, W, "fastrand")
@@ -93,9 +96,9 @@ def test_option_grid_keeps_the_shape_invariants():
                 if thr and info["column_ranges"] == 1:
                     assert info["long_row_threshold"] == thr
                 G, CH, V = info["lanes_per_row"], info["chunks_per_lane"], info["vector_width"]
-                assert info["rows_per_wave"] * G * info["edge_slots"] == 64
+                assert info["rows_per_wave"] * G * info["edge_slots"] == (64 * info["rows_per_wave"] if info["flattened"] else 64)
                 assert G * CH * V * info["grid_y"] >= F
-                groups = 4 if info["column_ranges"] == 8 else 1
+                groups = 4 if info["column_ranges"] == 8 and not info["flattened"] else 1
                 assert (info["grid_x"] - info["long_row_workgroups"]) * 4 * info["rows_per_wave"] * groups >= N
 
 
@@ -129,6 +132,25 @@ def test_column_partition_choice():
     assert forced["long_row_workgroups"] % 8 == 0
     assert es.es_spmm_launch_info(100, 5000, 64, 0, "full", opts=dict(column_partition=1))["column_ranges"] == 1
     assert es.es_spmm_launch_info(*dense, 64, 0, "full", backward=True)["column_ranges"] == 1
+
+
+def test_flattened_kernel_option():
+    for F, G in ((16, 4), (64, 16), (128, 32), (256, 64), (602, 64), (41, 16)):
+        info = es.es_spmm_launch_info(100_000, 1_000_000, F, 16, "fastrand", aligned16=(F % 4 == 0),
+                                      opts=dict(kernel=2, lanes_per_row=-1))
+        assert info["flattened"] == 1 and info["lanes_per_row"] == G and info["chunks_per_lane"] == 1
+        assert info["rows_per_wave"] == 256 // G and info["edge_slots"] == 64 // G
+        assert info["grid_y"] == -(-F // (4 * G))
+        _check(info, 100_000, F, False)
+    assert es.es_spmm_launch_info(1000, 5000, 3, 2, "bucket", opts=dict(kernel=2))["flattened"] == 0    # F < 4
+    assert es.es_spmm_launch_info(1000, 5000, 64, 2, "bucket", backward=True, opts=dict(kernel=2))["flattened"] == 0
+    assert es.es_spmm_launch_info(1000, 5000, 64, 2, "bucket", opts=dict(kernel=1))["flattened"] == 0
+    part = es.es_spmm_launch_info(10_000, 5_000_000, 64, 0, "full", opts=dict(kernel=2, column_partition=1))
+    assert part["flattened"] == 1 and part["column_ranges"] == 8 and part["long_row_workgroups"] == 0
+    fr = es.es_spmm_launch_info(10_000, 5_000_000, 64, 9, "fastrand", opts=dict(kernel=2, column_partition=1))
+    assert fr["flattened"] == 0 and fr["column_ranges"] == 8                # FastRand pieces: the row form
+    with pytest.raises(es.EsSpmmError):
+        es.es_spmm_launch_info(1000, 5000, 64, 2, "bucket", opts=dict(kernel=3))
 
 
 def test_bad_sizes_are_rejected():
