@@ -20,8 +20,9 @@ namespace {
 // no longer belong to one row) and lets the E edge slots walk it E entries per
 // step (stage 2).  Because of the padding a step never straddles two rows, so
 // "a new row starts here" is a wave-uniform bit per step (scalar test): at such
-// a step every slot adds its partial sums for the finished row into that row's
-// accumulator in LDS and starts over.  The rows' sums leave LDS once, at the
+// a step the slots' partial sums for the finished row are added across the wave
+// with lane swaps (LDS float atomics run about a lane per cycle here: far too
+// slow), written to that row's place in LDS, and the slots start over.  The rows' sums leave LDS once, at the
 // end: E rows per pass, coalesced (plain stores, or load-add-store in the later
 // phases of the column-partitioned product).
 // ---------------------------------------------------------------------------
@@ -31,15 +32,13 @@ constexpr int kFlatMaxRows = 64;
 
 struct FlatLds {                                      // one per wave
     uint2 tile[kFlatTile];                            // (row key, value)
-    float rowacc[kFlatAccFloats];                     // [NR][4G] sums of the chunk's rows
+    float rowacc[kFlatAccFloats];                     // [NR][4G] sums of the chunk's non-empty rows, in order
     int32_t start[kFlatMaxRows + 1];                  // padded start of each row in the run
     int32_t kept[kFlatMaxRows];                       // entries the row really keeps
     int32_t src[kFlatMaxRows];                        // CSR position of the row's (piece's) entry 0, < 2^31
     uint32_t len[kFlatMaxRows];                       // FastRand on a longer row: its length n; else 0
     uint32_t mul[kFlatMaxRows];                       //   multiplier P
     uint32_t rot[kFlatMaxRows];                       //   rotation off
-    uint32_t newrow[kFlatTile / 8];                   // bit u of word b: step 8b+u starts a row
-    uint8_t steprow[kFlatTile];                       // row (0..NR-1) a step belongs to, valid where a row starts
 };
 
 // What the chunk's rows are: whole sampled rows (forward kernel) or the pieces
@@ -49,15 +48,41 @@ struct FlatJob {
     bool accumulate;   // add to Y instead of overwriting it (phases after the first)
 };
 
+// Lanes whose bit BIT is clear get a + a', the others b + b', where a', b' are
+// the values of the lane that differs in that bit alone.  Bits 4 and 5 are the
+// row and half-wave swaps of gfx950 (odd rows of the first operand trade places
+// with even rows of the second; the upper half of the first with the lower half
+// of the second), bit 3 a rotation by 8 inside a row of 16; no LDS traffic.
+template <int BIT>
+__device__ __forceinline__ float halve_add(float a, float b, int lane)
+{
+    if constexpr (BIT == 5) {
+        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+        return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    } else if constexpr (BIT == 4) {
+        const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+        return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    } else {
+        const bool up = (lane >> BIT) & 1;
+        const float keep = up ? b : a, give = up ? a : b;
+        if constexpr (BIT == 3)
+            return keep + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(give), 0x128, 0xf, 0xf, true));
+        else
+            return keep + __shfl_xor(give, 1 << BIT, kWaveSize);
+    }
+}
+
 template <int G, bool ALIGNED, bool WIDE>
 __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const FlatJob job, FlatLds* lds_all)
 {
     constexpr int LOG_G = ilog2(G);
+    constexpr int LOG_E = 6 - LOG_G;
     constexpr int E = kWaveSize / G;                  // edge slots
     constexpr int NR = 4 * E;                         // rows per wave
     constexpr int FB = 4 * G;                         // feature columns per block
-    constexpr int U = 8;                              // loads in flight per lane
+    constexpr int U = E <= 8 ? 8 : kWaveSize / E;     // steps per batch = loads in flight per lane; U*E <= 64
     static_assert(NR * FB == kFlatAccFloats, "row accumulators fill their LDS array");
+    static_assert(U * E <= kWaveSize && kWaveSize % (U * E) == 0, "a batch lies inside 64 slots");
     using P = Pack<4, ALIGNED>;
     using K = RowKey<ALIGNED, WIDE>;
 
@@ -74,6 +99,7 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
     const int64_t r0 = ((int64_t)vb * kWavesPerBlock + wave) * NR;
     int32_t my_n = 0, my_k = 0;
     bool my_store = false;                            // this launch writes the row's Y
+    uint64_t nonempty;                                // bit j: row j has entries in this run
     {
         int32_t base = 0, lo = 0, hi = 0, kj = 0;
         bool strided = false;
@@ -95,6 +121,7 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
             }
             kj = hi - lo;
         }
+        nonempty = __ballot(kj > 0);
         const int32_t padded = (kj + E - 1) & ~(E - 1);
         int32_t incl = padded;                        // inclusive scan over the wave
 #pragma unroll
@@ -112,110 +139,133 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
         }
         if (lane == 0) s.start[0] = 0;
     }
-#pragma unroll
-    for (int i = 0; i < kFlatAccFloats / (4 * kWaveSize); ++i)
-        *reinterpret_cast<float4*>(&s.rowacc[(i * kWaveSize + lane) * 4]) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_fence();
     const int total = __builtin_amdgcn_readfirstlane(s.start[NR]);
 
     // ---- the run, tile by tile -----------------------------------------------------
     P acc;
     acc.zero();
-    int cur = -1;                                     // row being summed (wave-uniform)
+    int cur = -1;                                     // rank of the row being summed among the non-empty ones
     int jrow = 0;                                     // row of this lane's next slot (never decreases)
-    auto flush = [&](int row) {
-        if (row >= 0 && cols.ok[0]) {
-            float* dst = &s.rowacc[row * FB + l * 4];
-            atomicAdd(dst + 0, acc.v.x);
-            atomicAdd(dst + 1, acc.v.y);
-            atomicAdd(dst + 2, acc.v.z);
-            atomicAdd(dst + 3, acc.v.w);
+    // A row ends once.  Its sum over the slots is taken so that every halving
+    // step also halves what a lane carries: after two of them a lane holds one of
+    // the four columns, which the lanes of the lowest slots write side by side.
+    auto flush = [&]() {
+        float* dst = &s.rowacc[cur * FB + l * 4];
+        if constexpr (E == 1) {
+            *reinterpret_cast<float4*>(dst) = acc.v;
+        } else if constexpr (E == 2) {
+            const float s0 = halve_add<5>(acc.v.x, acc.v.z, lane);
+            const float s1 = halve_add<5>(acc.v.y, acc.v.w, lane);
+            *reinterpret_cast<float2*>(dst + 2 * e) = make_float2(s0, s1);
+        } else {
+            const float s0 = halve_add<LOG_G>(acc.v.x, acc.v.z, lane);
+            const float s1 = halve_add<LOG_G>(acc.v.y, acc.v.w, lane);
+            float v = halve_add<LOG_G + 1>(s0, s1, lane);
+            if constexpr (LOG_E > 2) v = halve_add<LOG_G + 2>(v, v, lane);
+            if constexpr (LOG_E > 3) v = halve_add<LOG_G + 3>(v, v, lane);
+            if ((e >> 2) == 0) dst[2 * (e & 1) + ((e >> 1) & 1)] = v;
         }
     };
     for (int t0 = 0; t0 < total; t0 += kFlatTile) {
         const int count = min(total - t0, kFlatTile);             // a multiple of E
-        if (lane < kFlatTile / 8) s.newrow[lane] = 0u;
-        wave_lds_fence();
-        // stage 1: slot -> (row, slot in row) -> sample index -> (key, value)
+        // stage 1: slot -> (row, slot in row) -> sample index -> (key, value).  No
+        // branch encloses a global load (lanes past the end redo the last slot), so
+        // that all of a lane's loads are in flight together.
+        constexpr int M = kFlatTile / kWaveSize;
+        int64_t pos[M];
+        bool real[M];
+        uint64_t firsts[M];                                       // bit i: slot 64m + i is the first of its row
 #pragma unroll
-        for (int m = 0; m < kFlatTile / kWaveSize; ++m) {
-            const int at = m * kWaveSize + lane;
-            if (at < count) {
-                const int sl = t0 + at;
-                while (sl >= s.start[jrow + 1]) ++jrow;           // sl < total = start[NR]: stops at NR-1
-                const int i = sl - s.start[jrow];
-                const bool real = i < s.kept[jrow];
-                const uint32_t n = s.len[jrow];
-                const uint32_t slot = real ? (uint32_t)i : 0u;    // padding repeats the row's first entry
-                uint32_t entry = slot;
-                if (n) {
-                    const uint32_t step = a.W < (1 << 22) ? (slot * s.mul[jrow]) % n
-                                                          : (uint32_t)(((uint64_t)slot * s.mul[jrow]) % n);
-                    entry = s.rot[jrow] + step;                   // both < n < 2^31
-                    if (entry >= n) entry -= n;
-                }
-                const int64_t p = (int64_t)s.src[jrow] + entry;
-                const float v = real ? (a.vals ? a.vals[p] : 1.0f) : 0.0f;
-                s.tile[at] = make_uint2(K::make(a.colidx[p], a.stride_units), __float_as_uint(v));
-                if (i == 0) {                                      // first slot of a row: its step starts the row
-                    const int step = at >> (6 - LOG_G);            // at / E
-                    atomicOr(&s.newrow[step >> 3], 1u << (step & 7));
-                    s.steprow[step] = (uint8_t)jrow;
-                }
+        for (int m = 0; m < M; ++m) {
+            const int at = min(m * kWaveSize + lane, count - 1);
+            const int sl = t0 + at;
+            while (sl >= s.start[jrow + 1]) ++jrow;               // sl < total = start[NR]: stops at NR-1
+            const int i = sl - s.start[jrow];
+            real[m] = i < s.kept[jrow];
+            firsts[m] = __ballot(i == 0 && m * kWaveSize + lane < count);
+            const uint32_t n = s.len[jrow];
+            const uint32_t slot = real[m] ? (uint32_t)i : 0u;     // padding repeats the row's first entry
+            uint32_t entry = slot;
+            if (n) {
+                const uint32_t step = a.W < (1 << 22) ? (slot * s.mul[jrow]) % n
+                                                      : (uint32_t)(((uint64_t)slot * s.mul[jrow]) % n);
+                entry = s.rot[jrow] + step;                       // both < n < 2^31
+                if (entry >= n) entry -= n;
             }
+            pos[m] = (int64_t)s.src[jrow] + entry;
+        }
+        int32_t col[M];
+        float val[M];
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            col[m] = a.colidx[pos[m]];
+            val[m] = a.vals ? a.vals[pos[m]] : 1.0f;
+        }
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            const int at = m * kWaveSize + lane;
+            if (at < count)
+                s.tile[at] = make_uint2(K::make(col[m], a.stride_units), __float_as_uint(real[m] ? val[m] : 0.0f));
         }
         wave_lds_fence();
-        // stage 2: E entries per step, U steps per batch
-        const int steps = count >> (6 - LOG_G);
+        // stage 2: E entries per step, U steps per batch.  A short last batch repeats
+        // the tile's last step with zero values instead of branching around loads.
+        // Rows start at multiples of E, so "step b0 + u starts a row" is bit
+        // (b0 + u) * E of the tile's first-slot bits: a scalar test.
+        const int steps = count >> LOG_E;
         for (int b0 = 0; b0 < steps; b0 += U) {
-            const uint32_t starts = __builtin_amdgcn_readfirstlane(s.newrow[b0 >> 3]);
-            const int nu = min(U, steps - b0);
+            const int slot0 = b0 << LOG_E;
+            uint64_t word = firsts[0];
+#pragma unroll
+            for (int m = 1; m < M; ++m)
+                if ((slot0 >> 6) == m) word = firsts[m];
+            const uint64_t starts = word >> (slot0 & 63);
             uint2 ed[U];
             P x[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (u < nu) {
-                    ed[u] = s.tile[(b0 + u) * E + e];
-                    x[u].load(K::row(a.X, ed[u].x, a.ldx) + cols.off[0]);
-                }
-            }
+            for (int u = 0; u < U; ++u) ed[u] = s.tile[min(b0 + u, steps - 1) * E + e];
+#pragma unroll
+            for (int u = 0; u < U; ++u) x[u].load(K::row(a.X, ed[u].x, a.ldx) + cols.off[0]);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (u < nu) {
-                    if (starts & (1u << u)) {                      // wave-uniform
-                        flush(cur);
-                        acc.zero();
-                        cur = __builtin_amdgcn_readfirstlane((int)s.steprow[b0 + u]);
-                    }
-                    acc.fma(__uint_as_float(ed[u].y), x[u]);
+                if ((starts >> (u * E)) & 1) {                     // wave-uniform; never set past the last step
+                    if (cur >= 0) flush();
+                    acc.zero();
+                    ++cur;
                 }
+                acc.fma(b0 + u < steps ? __uint_as_float(ed[u].y) : 0.0f, x[u]);
             }
         }
         wave_lds_fence();
     }
-    flush(cur);
+    if (cur >= 0) flush();
     wave_lds_fence();
 
-    // ---- rows out: E rows per pass ---------------------------------------------------
+    // ---- rows out: E rows per pass (earlier partial sums requested for all passes first) ----
+    constexpr int PASSES = NR / E;
+    P prev[PASSES];
+    if (job.accumulate) {
 #pragma unroll
-    for (int pass = 0; pass < NR / E; ++pass) {
+        for (int pass = 0; pass < PASSES; ++pass) {
+            const int64_t r = min(r0 + pass * E + e, a.N - 1);     // past the end: any valid row, unused
+            prev[pass].load(a.Y + r * (int64_t)a.ldy + cols.off[0]);
+        }
+    }
+#pragma unroll
+    for (int pass = 0; pass < PASSES; ++pass) {
         const int j = pass * E + e;
         const int64_t r = r0 + j;
         const int32_t n = __shfl(my_n, j, kWaveSize);
         const int32_t k = __shfl(my_k, j, kWaveSize);
         const bool store = __shfl((int)my_store, j, kWaveSize) != 0;
-        if (store && cols.ok[0]) {
-            P out;
-            out.v = *reinterpret_cast<const float4*>(&s.rowacc[j * FB + l * 4]);
-            if (a.norm != ES_NORM_NONE) out.scale(row_factor(a.norm, n, k));
-            float* y = a.Y + r * (int64_t)a.ldy + cols.off[0];
-            if (job.accumulate) {
-                P prev;
-                prev.load(y);
-                out.add(prev);
-            }
-            out.store(y, cols.first[0]);
-        }
+        const int rank = __popcll(nonempty & ((1ull << j) - 1ull));
+        P out;
+        out.zero();
+        if ((nonempty >> j) & 1) out.v = *reinterpret_cast<const float4*>(&s.rowacc[rank * FB + l * 4]);
+        if (a.norm != ES_NORM_NONE) out.scale(row_factor(a.norm, n, k));
+        if (job.accumulate) out.add(prev[pass]);
+        if (store && cols.ok[0]) out.store(a.Y + r * (int64_t)a.ldy + cols.off[0], cols.first[0]);
     }
 }
 

@@ -271,9 +271,9 @@ size_t part_workspace_bytes(int64_t N)
 
 // Whether to run the column-partitioned product.  It pays when a row's piece
 // inside one column range is long enough to amortise the extra pass over Y
-// (kept entries per row well above kParts) and when an XCD's eighth of the
-// column slice of X comes near the size of its L2 while the whole slice does
-// not fit: then most gathers hit the L2 instead of missing it.
+// (kept entries per row well above kParts) and when an XCD's eighth of a
+// 32-column slice of X is of the order of its L2 (measured gains on the dense
+// social-like graph from 58k to 699k rows, i.e. shares of 0.9 to 11 MB).
 bool pick_partition(int64_t N, double mean_kept, int32_t mode, int cols_per_block, int force)
 {
     if (mode == ES_BUCKET) return false;       // first-W entries crowd into the lowest column range
@@ -286,20 +286,7 @@ bool pick_partition(int64_t N, double mean_kept, int32_t mode, int cols_per_bloc
     if (mode == ES_FASTRAND) return false;
     if (mean_kept < 128.0) return false;
     const double share = (double)N * cols_per_block * 4.0 / kParts;
-    return share >= 1.0e6 && share <= 12.0e6;
-}
-
-// Whether to run the flattened kernel.  It takes the per-row instructions and
-// the lanes idled by unequal row lengths out, which pays while a row (or its
-// piece of a column range) keeps at most a few batches of entries; long rows
-// amortise all of that by themselves and the row kernel's long-row split suits
-// them better.
-bool pick_flat(double mean_kept, bool partition, int force)
-{
-    if (force == 1) return false;
-    if (force == 2) return true;
-    (void)mean_kept; (void)partition;
-    return false;
+    return share >= 0.5e6 && share <= 12.0e6;
 }
 
 int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool aligned, bool backward,
@@ -317,25 +304,46 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
     const double mean_stored = mean;
     if (mode != ES_FULL && mean > (double)W) mean = (double)W;
 
-    // Column-partitioned product?  Decided on 64-column slices, its best width.
-    const int slice_cols = F < 64 ? s.G * s.CH * s.vec : 64;
+    // Column-partitioned product?  Decided on 32-column slices, its best width on
+    // all but the smallest tables.
+    const int slice_cols = F < 32 ? s.G * s.CH * s.vec : 32;
     p->partition = !backward && have_workspace && pick_partition(N, mean, mode, slice_cols, ov.partition);
 
+    // The flattened kernel applies to 128-bit accesses; FastRand in the
+    // partitioned product needs the row kernel's per-row walk over all W slots.
+    const bool flat_applies = !backward && s.vec == 4 && !(p->partition && mode == ES_FASTRAND);
+    const bool flat_allowed = flat_applies && ov.kernel != 1;
+
     // Column slicing: fewer lanes across the feature columns, the rows swept once
-    // per slice, so that the part of X in use at a time is smaller.  Measured
-    // gains (profiles/): 64-column slices in the partitioned product for F > 64;
-    // 64-column slices on tables beyond ~0.5 GB (the co-purchase graph's
-    // community of X rows then comes nearer to an L2); 32-column slices for
-    // Bucket on rows several times longer than W (its picks crowd into the
-    // lowest-numbered columns).  Elsewhere slicing only re-reads the CSR entries.
+    // per slice, so that the part of X in use at a time is smaller.  A slice makes
+    // every row short, which the row kernel pays for per row and the flattened
+    // kernel does not; so the narrow (32-column) slices go with the flattened
+    // kernel.  Measured (profiles/):
+    //  * partitioned product: 32-column slices on the flattened kernel once an
+    //    XCD's share of a 64-column slice no longer fits its L2 (1.07x..1.3x over
+    //    64-column slices on the row kernel, which stay best below that);
+    //  * tables of 0.3 GB and more with F >= 128: 32-column slices on the
+    //    flattened kernel (1.08x..1.2x where column ids cluster, so that the X rows
+    //    of a community come nearer to an L2; 0.98x..1.0x where they do not);
+    //    with the row kernel forced, 64-column slices from 0.5 GB;
+    //  * Bucket on rows several times longer than W: 32-column slices (its picks
+    //    crowd into the lowest-numbered columns).
+    // Elsewhere slicing only re-reads the CSR entries.
     int slice_G = 0;
     bool sliced_by_rule = false;
+    bool want_flat = false;
     if (!backward && s.vec == 4) {
         if (ov.G > 0) slice_G = ov.G;
         else if (ov.G == 0) {
-            if (p->partition) slice_G = 16;
-            else if (mode == ES_BUCKET && F >= 64 && mean_stored >= 4.0 * W) slice_G = 8;
-            else if (F >= 128 && (double)N * F * 4.0 >= 512.0e6) slice_G = 16;
+            const double table = (double)N * F * 4.0;
+            if (p->partition) {
+                want_flat = flat_allowed && (double)N * 32.0 > 4.0e6;
+                slice_G = want_flat ? 8 : 16;
+            } else if (flat_allowed && F >= 128 && table >= 300.0e6) {
+                want_flat = true;
+                slice_G = 8;
+            } else if (mode == ES_BUCKET && F >= 64 && mean_stored >= 4.0 * W) slice_G = 8;
+            else if (F >= 128 && table >= 512.0e6) slice_G = 16;
             sliced_by_rule = slice_G > 0 && slice_G < s.G;
         }
     }
@@ -343,10 +351,9 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
         s.G = slice_G;                                     // narrower column blocks, more of them
         s.CH = 1;
     }
-    // Flattened kernel: applies to 128-bit accesses; its row accumulators hold one
-    // column block of at most 256 columns, so wider rows are sliced to that.
-    const bool flat_applies = !backward && s.vec == 4 && !(p->partition && mode == ES_FASTRAND);
-    p->flat = flat_applies && pick_flat(mean, p->partition, ov.kernel);
+    // The flattened kernel's row accumulators hold one column block of at most
+    // 256 columns, so wider rows are sliced to that.
+    p->flat = flat_applies && (ov.kernel == 2 || (ov.kernel == 0 && want_flat));
     if (p->flat) s.CH = 1;
     p->s = s;
 

@@ -944,6 +944,23 @@ def test_flattened_kernel_full_size(es, cfg):
         _say(f"cfg3 flattened exact product without column ranges: max normalised error {worst:.2e}")
 
 
+@pytest.mark.parametrize("cfg", [3, 4])
+def test_row_kernel_forced_full_size(es, cfg):
+    """The row kernel forced on where the library would by itself run the
+    flattened one (config 4 at every width, config 3's partitioned exact product):
+    every element of Y against the oracle."""
+    from gpu_util import DeviceCSR, check_every_element
+    w = _workload(cfg)
+    d = DeviceCSR(w.rowptr, w.colidx, w.vals, w.X).with_workspace()
+    assert es.es_spmm_launch_info(w.N, w.nnz, w.F, 0, "full")["flattened"] == 1
+    assert es.es_spmm_launch_info(w.N, w.nnz, w.F, 0, "full", opts=dict(kernel=1))["flattened"] == 0
+    cases = [("full", 0)] if cfg == 3 else [("fastrand", w.Ws[0]), ("bucket", w.Ws[-1]), ("full", 0)]
+    for mode, W in cases:
+        worst = check_every_element(d, W, mode, 0, what=f"cfg{cfg} row kernel {mode} W={W}",
+                                    opts=dict(workspace=d.default_ws, kernel=1))
+        _say(f"cfg{cfg} row kernel {mode} W={W}: max normalised error {worst:.2e}")
+
+
 def test_config3_column_partitioned(es):
     """Config 3 through es_spmm_ws (the library itself chooses the column-
     partitioned product here): every element against the oracle, and the result

@@ -127,11 +127,32 @@ def test_column_partition_choice():
     assert es.es_spmm_launch_info(*dense, 64, 0, "full", opts=dict(column_partition=-1))["column_ranges"] == 1
     assert es.es_spmm_launch_info(170_000, 2_370_240, 128, 0, "full")["column_ranges"] == 1      # 14 per row
     assert es.es_spmm_launch_info(2_450_000, 119_569_270, 128, 0, "full")["column_ranges"] == 1  # X far too big
-    forced = es.es_spmm_launch_info(170_000, 2_370_240, 128, 0, "full", opts=dict(column_partition=1))
+    forced = es.es_spmm_launch_info(170_000, 2_370_240, 128, 0, "full", opts=dict(column_partition=1, kernel=1))
     assert forced["column_ranges"] == 8 and forced["long_row_workgroups"] * 2 == forced["grid_x"]
-    assert forced["long_row_workgroups"] % 8 == 0
+    assert forced["long_row_workgroups"] % 8 == 0 and forced["lanes_per_row"] == 16
+    forced = es.es_spmm_launch_info(170_000, 2_370_240, 128, 0, "full", opts=dict(column_partition=1))
+    assert forced["column_ranges"] == 8 and forced["flattened"] == 1 and forced["lanes_per_row"] == 8
     assert es.es_spmm_launch_info(100, 5000, 64, 0, "full", opts=dict(column_partition=1))["column_ranges"] == 1
     assert es.es_spmm_launch_info(*dense, 64, 0, "full", backward=True)["column_ranges"] == 1
+
+
+def test_flattened_kernel_choice():
+    """Without options the flattened kernel runs where narrow column slices pay:
+    the partitioned product once a 64-column share outgrows an L2, and tables of
+    0.3 GB and more with F >= 128; the row kernel everywhere else."""
+    big = es.es_spmm_launch_info(2_450_000, 119_569_270, 128, 32, "fastrand")
+    assert big["flattened"] == 1 and big["lanes_per_row"] == 8 and big["grid_y"] == 4 and big["rows_per_wave"] == 32
+    assert es.es_spmm_launch_info(2_450_000, 119_569_270, 128, 0, "full")["flattened"] == 1
+    row = es.es_spmm_launch_info(2_450_000, 119_569_270, 128, 32, "fastrand", opts=dict(kernel=1))
+    assert row["flattened"] == 0 and row["lanes_per_row"] == 16
+    dense = es.es_spmm_launch_info(233_000, 113_134_823, 64, 0, "full")
+    assert dense["flattened"] == 1 and dense["column_ranges"] == 8 and dense["lanes_per_row"] == 8
+    small = es.es_spmm_launch_info(58_250, 27_659_516, 64, 0, "full")
+    assert small["flattened"] == 0 and small["column_ranges"] == 8 and small["lanes_per_row"] == 16
+    assert es.es_spmm_launch_info(233_000, 113_134_823, 64, 64, "fastrand")["flattened"] == 0
+    assert es.es_spmm_launch_info(233_000, 113_134_823, 256, 64, "fastrand")["flattened"] == 0   # 0.24 GB table
+    assert es.es_spmm_launch_info(170_000, 2_370_240, 128, 16, "bucket")["flattened"] == 0
+    assert es.es_spmm_launch_info(2_450_000, 119_569_270, 128, 32, "fastrand", backward=True)["flattened"] == 0
 
 
 def test_flattened_kernel_option():
