@@ -115,8 +115,8 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
                 strided = a.mode == ES_FASTRAND && my_n > a.W;
             } else {
                 const int32_t* cr = a.cuts + r * kParts;
-                lo = cr[job.part];
-                hi = (job.part + 1 < kParts) ? cr[job.part + 1] : my_n;
+                lo = __builtin_nontemporal_load(&cr[job.part]);
+                hi = (job.part + 1 < kParts) ? __builtin_nontemporal_load(&cr[job.part + 1]) : my_n;
                 my_store = !job.accumulate || hi > lo;
             }
             kj = hi - lo;
@@ -167,25 +167,32 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
             if ((e >> 2) == 0) dst[2 * (e & 1) + ((e >> 1) & 1)] = v;
         }
     };
-    for (int t0 = 0; t0 < total; t0 += kFlatTile) {
-        const int count = min(total - t0, kFlatTile);             // a multiple of E
-        // stage 1: slot -> (row, slot in row) -> sample index -> (key, value).  No
-        // branch encloses a global load (lanes past the end redo the last slot), so
-        // that all of a lane's loads are in flight together.
-        constexpr int M = kFlatTile / kWaveSize;
-        int64_t pos[M];
+    // Stage 1 for one tile, up to the loads: slot -> (row, slot in row) -> sample
+    // index -> CSR position, then the entry's column and value requested.  No
+    // branch encloses a global load (lanes past the tile's end redo its last
+    // slot; past the run's end, the run's last slot), so that all of a lane's
+    // loads are in flight together, and the next tile's are in flight while this
+    // tile is consumed.
+    constexpr int M = kFlatTile / kWaveSize;
+    struct Staged {
+        int32_t col[M];
+        float val[M];
         bool real[M];
         uint64_t firsts[M];                                       // bit i: slot 64m + i is the first of its row
+    };
+    auto request = [&](int t0, Staged& st) {
+        const int count = min(total - t0, kFlatTile);             // a multiple of E; <= 0 past the run
+        int64_t pos[M];
 #pragma unroll
         for (int m = 0; m < M; ++m) {
             const int at = min(m * kWaveSize + lane, count - 1);
-            const int sl = t0 + at;
+            const int sl = t0 + at;                               // t0 - 1 at least: a slot of the run
             while (sl >= s.start[jrow + 1]) ++jrow;               // sl < total = start[NR]: stops at NR-1
             const int i = sl - s.start[jrow];
-            real[m] = i < s.kept[jrow];
-            firsts[m] = __ballot(i == 0 && m * kWaveSize + lane < count);
+            st.real[m] = i < s.kept[jrow];
+            st.firsts[m] = __ballot(i == 0 && m * kWaveSize + lane < count);
             const uint32_t n = s.len[jrow];
-            const uint32_t slot = real[m] ? (uint32_t)i : 0u;     // padding repeats the row's first entry
+            const uint32_t slot = st.real[m] ? (uint32_t)i : 0u;  // padding repeats the row's first entry
             uint32_t entry = slot;
             if (n) {
                 const uint32_t step = a.W < (1 << 22) ? (slot * s.mul[jrow]) % n
@@ -195,38 +202,49 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
             }
             pos[m] = (int64_t)s.src[jrow] + entry;
         }
-        int32_t col[M];
-        float val[M];
 #pragma unroll
         for (int m = 0; m < M; ++m) {
-            col[m] = a.colidx[pos[m]];
-            val[m] = a.vals ? a.vals[pos[m]] : 1.0f;
+            st.col[m] = __builtin_nontemporal_load(&a.colidx[pos[m]]);
+            st.val[m] = a.vals ? __builtin_nontemporal_load(&a.vals[pos[m]]) : 1.0f;
         }
+    };
+    Staged st;
+    if (total > 0) request(0, st);                                // an empty run has no slot to stand in for
+    for (int t0 = 0; t0 < total; t0 += kFlatTile) {
+        const int count = min(total - t0, kFlatTile);
+        uint64_t firsts[M];
 #pragma unroll
         for (int m = 0; m < M; ++m) {
+            firsts[m] = st.firsts[m];
             const int at = m * kWaveSize + lane;
             if (at < count)
-                s.tile[at] = make_uint2(K::make(col[m], a.stride_units), __float_as_uint(real[m] ? val[m] : 0.0f));
+                s.tile[at] = make_uint2(K::make(st.col[m], a.stride_units),
+                                        __float_as_uint(st.real[m] ? st.val[m] : 0.0f));
         }
         wave_lds_fence();
-        // stage 2: E entries per step, U steps per batch.  A short last batch repeats
-        // the tile's last step with zero values instead of branching around loads.
-        // Rows start at multiples of E, so "step b0 + u starts a row" is bit
-        // (b0 + u) * E of the tile's first-slot bits: a scalar test.
+        request(t0 + kFlatTile, st);
+        // stage 2: E entries per step, U steps per batch, a batch's rows of X in
+        // flight together.  Rows start at multiples of E, so
+        // "step b + u starts a row" is bit (b + u) * E of the tile's first-slot bits:
+        // a scalar test.
         const int steps = count >> LOG_E;
-        for (int b0 = 0; b0 < steps; b0 += U) {
-            const int slot0 = b0 << LOG_E;
+        auto fetch = [&](int b, P (&x)[U]) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t key = s.tile[min(b + u, steps - 1) * E + e].x;
+                x[u].load(K::row(a.X, key, a.ldx) + cols.off[0]);
+            }
+        };
+        auto consume = [&](int b, P (&x)[U]) {
+            const int slot0 = b << LOG_E;
             uint64_t word = firsts[0];
 #pragma unroll
             for (int m = 1; m < M; ++m)
                 if ((slot0 >> 6) == m) word = firsts[m];
             const uint64_t starts = word >> (slot0 & 63);
-            uint2 ed[U];
-            P x[U];
+            float v[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) ed[u] = s.tile[min(b0 + u, steps - 1) * E + e];
-#pragma unroll
-            for (int u = 0; u < U; ++u) x[u].load(K::row(a.X, ed[u].x, a.ldx) + cols.off[0]);
+            for (int u = 0; u < U; ++u) v[u] = __uint_as_float(s.tile[min(b + u, steps - 1) * E + e].y);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if ((starts >> (u * E)) & 1) {                     // wave-uniform; never set past the last step
@@ -234,8 +252,13 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
                     acc.zero();
                     ++cur;
                 }
-                acc.fma(b0 + u < steps ? __uint_as_float(ed[u].y) : 0.0f, x[u]);
+                acc.fma(b + u < steps ? v[u] : 0.0f, x[u]);        // a short last batch repeats the last step
             }
+        };
+        P x[U];
+        for (int b0 = 0; b0 < steps; b0 += U) {
+            fetch(b0, x);
+            consume(b0, x);
         }
         wave_lds_fence();
     }
@@ -249,7 +272,7 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
 #pragma unroll
         for (int pass = 0; pass < PASSES; ++pass) {
             const int64_t r = min(r0 + pass * E + e, a.N - 1);     // past the end: any valid row, unused
-            prev[pass].load(a.Y + r * (int64_t)a.ldy + cols.off[0]);
+            prev[pass].load_streaming(a.Y + r * (int64_t)a.ldy + cols.off[0]);
         }
     }
 #pragma unroll
@@ -265,7 +288,10 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
         if ((nonempty >> j) & 1) out.v = *reinterpret_cast<const float4*>(&s.rowacc[rank * FB + l * 4]);
         if (a.norm != ES_NORM_NONE) out.scale(row_factor(a.norm, n, k));
         if (job.accumulate) out.add(prev[pass]);
-        if (store && cols.ok[0]) out.store(a.Y + r * (int64_t)a.ldy + cols.off[0], cols.first[0]);
+        if (store && cols.ok[0]) {
+            float* y = a.Y + r * (int64_t)a.ldy + cols.off[0];
+            out.store_streaming(y, cols.first[0]);                 // not read again by this launch
+        }
     }
 }
 

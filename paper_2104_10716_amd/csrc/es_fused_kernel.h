@@ -87,7 +87,7 @@ __device__ __forceinline__ void row_block(const Args& a, uint32_t vb, uint2* lds
         }
 #pragma unroll
         for (int ch = 0; ch < CH; ++ch)
-            if (cols.ok[ch]) acc[ch].store(y + cols.off[ch], cols.first[ch]);
+            if (cols.ok[ch]) acc[ch].store_streaming(y + cols.off[ch], cols.first[ch]);
     }
 }
 

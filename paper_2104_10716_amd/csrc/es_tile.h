@@ -39,6 +39,28 @@ template <bool ALIGNED> struct Pack<4, ALIGNED> {
             p[3] = v.w;
         }
     }
+    // as load(), marked as data this kernel reads once
+    __device__ __forceinline__ void load_streaming(const float* p)
+    {
+        if (ALIGNED) {
+            typedef float float4_v __attribute__((ext_vector_type(4)));
+            const float4_v t = __builtin_nontemporal_load(reinterpret_cast<const float4_v*>(p));
+            v = make_float4(t.x, t.y, t.z, t.w);
+        } else {
+            load(p);
+        }
+    }
+    // as store(), marked as data this kernel will not read again (kept out of the way of X in the L2)
+    __device__ __forceinline__ void store_streaming(float* p, int first) const
+    {
+        if (ALIGNED) {
+            typedef float float4_v __attribute__((ext_vector_type(4)));
+            float4_v t = {v.x, v.y, v.z, v.w};
+            __builtin_nontemporal_store(t, reinterpret_cast<float4_v*>(p));
+        } else {
+            store(p, first);
+        }
+    }
     __device__ __forceinline__ void atomic_add(float* p, int first) const
     {
         if (first <= 0) unsafeAtomicAdd(p, v.x);
@@ -64,6 +86,7 @@ template <bool ALIGNED> struct Pack<1, ALIGNED> {
     __device__ __forceinline__ void zero() { v = 0.f; }
     __device__ __forceinline__ void load(const float* p) { v = *p; }
     __device__ __forceinline__ void store(float* p, int) const { *p = v; }
+    __device__ __forceinline__ void store_streaming(float* p, int) const { __builtin_nontemporal_store(v, p); }
     __device__ __forceinline__ void atomic_add(float* p, int) const { unsafeAtomicAdd(p, v); }
     __device__ __forceinline__ void fma(float a, const Pack& x) { v = fmaf(a, x.v, v); }
     __device__ __forceinline__ void scale(float f) { v *= f; }
