@@ -360,7 +360,7 @@ def calibrate_gather(dev):
     g = torch.Generator(device=dev)
     g.manual_seed(99)
     for F in (64, 128, 256):
-        for mb in (32, 64, 128, 256, 1024):
+        for mb in (8, 16, 32, 64, 128, 256, 1024):
             N = (mb << 20) // (4 * F)
             rowptr = (torch.arange(N + 1, dtype=torch.int64, device=dev) * deg).to(torch.int32)
             X = torch.ones((N, F), dtype=torch.float32, device=dev)
@@ -403,7 +403,7 @@ def main() -> int:
                     help="first run kernels of known traffic (1 GiB copies, a strided-read probe) that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     ap.add_argument("--calibrate-gather", action="store_true",
-                    help="also time random row gathers of 32 MB - 1 GB tables (context for the rates)")
+                    help="also time random row gathers of 8 MB - 1 GB tables (context for the rates)")
     ap.add_argument("--mark-calls", action="store_true",
                     help="launch a tiny int16 fill before every es_spmm call so that a counter run's "
                          "dispatch list can be cut into calls (adds launch gaps: not for timing)")
@@ -455,6 +455,19 @@ def main() -> int:
     step_traffic = (sum(traffic_calls[call_label(*c)]["fetch_bytes"] + traffic_calls[call_label(*c)]["write_bytes"]
                         for c in calls) if have_traffic else None)
 
+    # which kernel serves each call (as rocprofv3 names it, template arguments cut to the lane count)
+    def kernel_of(mode, W):
+        info = es.es_spmm_launch_info(dw.N, dw.nnz, dw.F, W, mode, ldx=dw.X.stride(0), ldy=dw.Y.stride(0),
+                                      aligned16=(dw.F % 4 == 0 and dw.X.stride(0) % 4 == 0))
+        if info["column_ranges"] > 1:
+            base = "es_spmm_part_flat_kernel" if info["flattened"] else "es_spmm_part_kernel"
+        else:
+            base = "es_spmm_flat_kernel" if info["flattened"] else "es_spmm_kernel"
+        return f"{base}<{info['lanes_per_row']}, ...>"
+    call_kernels = {call_label(*c): kernel_of(*c) for c in calls}
+    names = list(call_kernels.values())
+    main_kernel = max(set(names), key=names.count)
+
     marker = torch.empty(1, dtype=torch.int16, device=dev)      # fill_ on it: FillFunctor<short>, used nowhere else
 
     def step():
@@ -492,7 +505,7 @@ def main() -> int:
         "achieved": round(cmin, 1), "frac": round(cmin / HBM_PEAK_GBPS, 4),
         "bytes": "B_min: rowptr + kept (column, value) pairs + each DISTINCT kept column's row of X once + Y once",
         "bytes_per_launch": int(step_B_min / len(calls)),
-        "kernel": "es_spmm_kernel", "launch_ms": round(kernel_ms, 5),
+        "kernel": main_kernel, "kernel_of_call": call_kernels, "launch_ms": round(kernel_ms, 5),
         "traffic": None if step_traffic is None else int(step_traffic / len(calls)),
         "traffic_source": traffic_meta,
         "rates_GBps": {
