@@ -541,13 +541,14 @@ def main() -> int:
         result["cpu_baseline"] = cpu_baseline(dw, calls)
         log(f"cpu baseline: {result['cpu_baseline']}")
 
+    if args.calibrate_gather:
+        result["gather_calibration"] = calibrate_gather(dev)
+
     if not args.main_only:
         flush = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device=dev)   # 1 GiB
         flush.zero_()
         result["calls"] = per_call_table(dw, calls, 20, flush, 5, traffic_calls, L)
         log_rows(f"cfg{args.config}", result["calls"])
-        if args.calibrate_gather:
-            result["gather_calibration"] = calibrate_gather(dev)
         extra = [tiny_config1(dev)]
         for cfg in (2, 3, 4):
             if cfg == args.config:

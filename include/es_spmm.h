@@ -280,9 +280,11 @@ typedef struct {
                                     the library decides from N, F, W and nnz / N      */
     int32_t kernel;              /* 1 = the row kernel (a row, or a row per team of
                                     lanes, on a wave at a time); 2 = the flattened
-                                    kernel (a wave lays 256 / lanes_per_row rows end
-                                    to end and deals their entries to its edge slots:
-                                    for short rows); falls back to 1 where 2 does not
+                                    kernel (a wave lays 64 or 128 / lanes_per_row rows
+                                    end to end and deals their entries to its edge
+                                    slots: for short rows and narrow column slices;
+                                    the library picks it by itself where that
+                                    measured faster); falls back to 1 where 2 does not
                                     apply (F < 4, the backward pass, FastRand in the
                                     column-partitioned product)                       */
 } es_launch_opts_t;

@@ -12,8 +12,8 @@ namespace {
 // differ in length idles the lanes of the short ones.  Short rows -- sampled
 // rows with W of 16..64, the eighth-of-a-row pieces of the column-partitioned
 // product, the rows of a column slice -- then run at the instruction rate, not
-// at the memory rate.  Here a wave takes NR = 4E consecutive rows (E = 64 / G
-// edge slots), lays their kept entries end to end (each row padded to a
+// at the memory rate.  Here a wave takes NR = E or 2E consecutive rows (E =
+// 64 / G edge slots), lays their kept entries end to end (each row padded to a
 // multiple of E with zero-valued repeats of its first entry), stages that run
 // tile by tile into LDS (stage 1 of Algorithm 1; the sample index of a slot is
 // evaluated from its definition, Equation 2, since consecutive slots of a lane
@@ -22,13 +22,15 @@ namespace {
 // "a new row starts here" is a wave-uniform bit per step (scalar test): at such
 // a step the slots' partial sums for the finished row are added across the wave
 // with lane swaps (LDS float atomics run about a lane per cycle here: far too
-// slow), written to that row's place in LDS, and the slots start over.  The rows' sums leave LDS once, at the
-// end: E rows per pass, coalesced (plain stores, or load-add-store in the later
-// phases of the column-partitioned product).
+// slow), written to that row's place in LDS, and the slots start over.  The
+// rows' sums leave LDS once, at the end: E rows per pass, coalesced (plain
+// stores, or load-add-store in the later phases of the column-partitioned
+// product).
 // ---------------------------------------------------------------------------
 constexpr int kFlatTile = 256;                        // staged entries per tile
-constexpr int kFlatAccFloats = 1024;                  // NR rows x 4G columns
-constexpr int kFlatMaxRows = 64;
+constexpr int kFlatPartRps = 2;                       // rows per edge slot in the column-partitioned product
+constexpr int kFlatAccFloats = 512;                   // NR rows x 4G columns at most
+constexpr int kFlatMaxRows = 32;                      // NR at most
 
 struct FlatLds {                                      // one per wave
     uint2 tile[kFlatTile];                            // (row key, value)
@@ -72,16 +74,30 @@ __device__ __forceinline__ float halve_add(float a, float b, int lane)
     }
 }
 
-template <int G, bool ALIGNED, bool WIDE>
+// v + the values of the lanes that differ from this one in bit BIT (2 or 3) and
+// agree in the lower ones: a rotation by 2^BIT inside a row of 16 lanes.  For
+// bit 2 the values must already be equal across bit 3.
+template <int BIT>
+__device__ __forceinline__ float all_add(float v)
+{
+    static_assert(BIT == 2 || BIT == 3, "rotations inside a row of 16");
+    constexpr int kRowRor = 0x120 + (1 << BIT);
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), kRowRor, 0xf, 0xf, true));
+}
+
+// RPS: rows per edge slot on a wave (NR = RPS * E rows per wave).  Fewer rows per
+// wave cost more set-up per row and even the waves out: 1 for the exact product
+// (its rows differ most in length), 2 for sampled rows.
+template <int G, bool ALIGNED, bool WIDE, bool STRIDED, int RPS>
 __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const FlatJob job, FlatLds* lds_all)
 {
     constexpr int LOG_G = ilog2(G);
     constexpr int LOG_E = 6 - LOG_G;
     constexpr int E = kWaveSize / G;                  // edge slots
-    constexpr int NR = 4 * E;                         // rows per wave
+    constexpr int NR = RPS * E;                       // rows per wave
     constexpr int FB = 4 * G;                         // feature columns per block
     constexpr int U = E <= 8 ? 8 : kWaveSize / E;     // steps per batch = loads in flight per lane; U*E <= 64
-    static_assert(NR * FB == kFlatAccFloats, "row accumulators fill their LDS array");
+    static_assert(NR * FB <= kFlatAccFloats && NR <= kFlatMaxRows, "row accumulators fit their LDS array");
     static_assert(U * E <= kWaveSize && kWaveSize % (U * E) == 0, "a batch lies inside 64 slots");
     using P = Pack<4, ALIGNED>;
     using K = RowKey<ALIGNED, WIDE>;
@@ -112,7 +128,7 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
                 hi = my_k;
                 my_store = my_k <= a.long_k;          // longer rows belong to the long-row part
                 if (!my_store) hi = 0;
-                strided = a.mode == ES_FASTRAND && my_n > a.W;
+                strided = STRIDED && my_n > a.W;
             } else {
                 const int32_t* cr = a.cuts + r * kParts;
                 lo = __builtin_nontemporal_load(&cr[job.part]);
@@ -133,9 +149,11 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
             s.start[lane + 1] = incl;
             s.kept[lane] = kj;
             s.src[lane] = base + lo;
-            s.len[lane] = strided ? (uint32_t)my_n : 0u;
-            s.mul[lane] = strided ? fastrand_multiplier((uint32_t)my_n) : 0u;
-            s.rot[lane] = strided ? fastrand_offset(a.seed, r, (uint32_t)my_n) : 0u;
+            if constexpr (STRIDED) {
+                s.len[lane] = strided ? (uint32_t)my_n : 0u;
+                s.mul[lane] = strided ? fastrand_multiplier((uint32_t)my_n) : 0u;
+                s.rot[lane] = strided ? fastrand_offset(a.seed, r, (uint32_t)my_n) : 0u;
+            }
         }
         if (lane == 0) s.start[0] = 0;
     }
@@ -147,9 +165,11 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
     acc.zero();
     int cur = -1;                                     // rank of the row being summed among the non-empty ones
     int jrow = 0;                                     // row of this lane's next slot (never decreases)
-    // A row ends once.  Its sum over the slots is taken so that every halving
-    // step also halves what a lane carries: after two of them a lane holds one of
-    // the four columns, which the lanes of the lowest slots write side by side.
+    // A row ends once.  Its sum over the slots is taken so that the two steps over
+    // the highest slot bits (lane bits 4 and 5: plain swaps) also halve what a lane
+    // carries: after them a lane holds one of the four columns; the lower slot bits
+    // are summed by rotations inside a row of 16 lanes.  The lanes of the slots
+    // whose low bits are zero write the four columns side by side.
     auto flush = [&]() {
         float* dst = &s.rowacc[cur * FB + l * 4];
         if constexpr (E == 1) {
@@ -159,12 +179,13 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
             const float s1 = halve_add<5>(acc.v.y, acc.v.w, lane);
             *reinterpret_cast<float2*>(dst + 2 * e) = make_float2(s0, s1);
         } else {
-            const float s0 = halve_add<LOG_G>(acc.v.x, acc.v.z, lane);
-            const float s1 = halve_add<LOG_G>(acc.v.y, acc.v.w, lane);
-            float v = halve_add<LOG_G + 1>(s0, s1, lane);
-            if constexpr (LOG_E > 2) v = halve_add<LOG_G + 2>(v, v, lane);
-            if constexpr (LOG_E > 3) v = halve_add<LOG_G + 3>(v, v, lane);
-            if ((e >> 2) == 0) dst[2 * (e & 1) + ((e >> 1) & 1)] = v;
+            const float s0 = halve_add<4>(acc.v.x, acc.v.z, lane);    // bit 4 clear: x, set: z
+            const float s1 = halve_add<4>(acc.v.y, acc.v.w, lane);    //              y       w
+            float v = halve_add<5>(s0, s1, lane);                     // bit 5 clear: s0, set: s1
+            if constexpr (LOG_E > 2) v = all_add<3>(v);
+            if constexpr (LOG_E > 3) v = all_add<2>(v);
+            const int top = e >> (LOG_E - 2);                         // lane bits 4, 5
+            if ((e & (E / 4 - 1)) == 0) dst[2 * (top & 1) + (top >> 1)] = v;
         }
     };
     // Stage 1 for one tile, up to the loads: slot -> (row, slot in row) -> sample
@@ -191,14 +212,16 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
             const int i = sl - s.start[jrow];
             st.real[m] = i < s.kept[jrow];
             st.firsts[m] = __ballot(i == 0 && m * kWaveSize + lane < count);
-            const uint32_t n = s.len[jrow];
             const uint32_t slot = st.real[m] ? (uint32_t)i : 0u;  // padding repeats the row's first entry
             uint32_t entry = slot;
-            if (n) {
-                const uint32_t step = a.W < (1 << 22) ? (slot * s.mul[jrow]) % n
-                                                      : (uint32_t)(((uint64_t)slot * s.mul[jrow]) % n);
-                entry = s.rot[jrow] + step;                       // both < n < 2^31
-                if (entry >= n) entry -= n;
+            if constexpr (STRIDED) {
+                const uint32_t n = s.len[jrow];
+                if (n) {
+                    const uint32_t step = a.W < (1 << 22) ? (slot * s.mul[jrow]) % n
+                                                          : (uint32_t)(((uint64_t)slot * s.mul[jrow]) % n);
+                    entry = s.rot[jrow] + step;                   // both < n < 2^31
+                    if (entry >= n) entry -= n;
+                }
             }
             pos[m] = (int64_t)s.src[jrow] + entry;
         }
@@ -212,53 +235,48 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
     if (total > 0) request(0, st);                                // an empty run has no slot to stand in for
     for (int t0 = 0; t0 < total; t0 += kFlatTile) {
         const int count = min(total - t0, kFlatTile);
+        // the tile is filled up to whole batches with zero-valued repeats of its last
+        // entry (what the lanes past its end requested), so stage 2 needs no bounds
+        const int filled = (count + U * E - 1) & ~(U * E - 1);
         uint64_t firsts[M];
 #pragma unroll
         for (int m = 0; m < M; ++m) {
             firsts[m] = st.firsts[m];
             const int at = m * kWaveSize + lane;
-            if (at < count)
+            if (at < filled)
                 s.tile[at] = make_uint2(K::make(st.col[m], a.stride_units),
-                                        __float_as_uint(st.real[m] ? st.val[m] : 0.0f));
+                                        __float_as_uint(at < count && st.real[m] ? st.val[m] : 0.0f));
         }
         wave_lds_fence();
         request(t0 + kFlatTile, st);
         // stage 2: E entries per step, U steps per batch, a batch's rows of X in
-        // flight together.  Rows start at multiples of E, so
-        // "step b + u starts a row" is bit (b + u) * E of the tile's first-slot bits:
-        // a scalar test.
+        // flight together.  Rows start at multiples of E, so "step b0 + u starts a
+        // row" is bit (b0 + u) * E of the tile's first-slot bits: a scalar test.
         const int steps = count >> LOG_E;
-        auto fetch = [&](int b, P (&x)[U]) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t key = s.tile[min(b + u, steps - 1) * E + e].x;
-                x[u].load(K::row(a.X, key, a.ldx) + cols.off[0]);
-            }
-        };
-        auto consume = [&](int b, P (&x)[U]) {
-            const int slot0 = b << LOG_E;
+        for (int b0 = 0; b0 < steps; b0 += U) {
+            const int slot0 = b0 << LOG_E;
             uint64_t word = firsts[0];
 #pragma unroll
             for (int m = 1; m < M; ++m)
                 if ((slot0 >> 6) == m) word = firsts[m];
             const uint64_t starts = word >> (slot0 & 63);
-            float v[U];
+            uint2 ed[U];
+            P x[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) v[u] = __uint_as_float(s.tile[min(b + u, steps - 1) * E + e].y);
+            for (int u = 0; u < U; ++u) ed[u] = s.tile[(b0 + u) * E + e];
+#pragma unroll
+            for (int u = 0; u < U; ++u) x[u].load(K::row(a.X, ed[u].x, a.ldx) + cols.off[0]);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
+                const float v = __uint_as_float(ed[u].y);
                 if ((starts >> (u * E)) & 1) {                     // wave-uniform; never set past the last step
                     if (cur >= 0) flush();
-                    acc.zero();
                     ++cur;
+                    acc.mul(v, x[u]);                              // the row's first step
+                } else {
+                    acc.fma(v, x[u]);
                 }
-                acc.fma(b + u < steps ? v[u] : 0.0f, x[u]);        // a short last batch repeats the last step
             }
-        };
-        P x[U];
-        for (int b0 = 0; b0 < steps; b0 += U) {
-            fetch(b0, x);
-            consume(b0, x);
         }
         wave_lds_fence();
     }
@@ -299,7 +317,7 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
 // a.long_blocks workgroups split the rows that keep more than a.long_k entries
 // (those rows are left out of the flattened runs), the rest serve 4 * NR rows
 // each, remapped so that every XCD walks one contiguous range of rows.
-template <int G, bool ALIGNED, bool WIDE>
+template <int G, bool ALIGNED, bool WIDE, bool STRIDED, int RPS>
 __global__ void __launch_bounds__(kBlockThreads) es_spmm_flat_kernel(const Args a)
 {
     constexpr size_t kLongBytes = kWavesPerBlock * kWaveTileStride * sizeof(uint2) + sizeof(LongScratch);
@@ -315,7 +333,7 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_flat_kernel(const Args 
     const uint32_t b = blockIdx.x - a.long_blocks;
     const uint32_t vb = (b % kNumXcd) * a.blocks_per_xcd + b / kNumXcd;
     if (vb >= a.nblocks) return;
-    flat_block<G, ALIGNED, WIDE>(a, vb, FlatJob{-1, false}, reinterpret_cast<FlatLds*>(raw));
+    flat_block<G, ALIGNED, WIDE, STRIDED, RPS>(a, vb, FlatJob{-1, false}, reinterpret_cast<FlatLds*>(raw));
 }
 
 // One phase of the column-partitioned exact product on flattened pieces (see
@@ -330,7 +348,7 @@ __global__ void __launch_bounds__(kBlockThreads) es_spmm_part_flat_kernel(const 
     const uint32_t sblock = (p + (uint32_t)a.phase) % kNumXcd;
     const uint32_t vb = sblock * a.blocks_per_xcd + q;
     if (vb >= a.nblocks) return;
-    flat_block<G, ALIGNED, WIDE>(a, vb, FlatJob{(int)p, a.phase != 0}, lds);
+    flat_block<G, ALIGNED, WIDE, false, kFlatPartRps>(a, vb, FlatJob{(int)p, a.phase != 0}, lds);
 }
 
 }  // namespace

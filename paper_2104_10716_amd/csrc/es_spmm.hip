@@ -142,7 +142,12 @@ hipError_t launch_flat(Args a, dim3 grid, bool partition, int32_t* cuts, hipStre
             const hipError_t err = hipGetLastError();
             if (err != hipSuccess) return err;
         }
-        hipLaunchKernelGGL((es_spmm_flat_kernel<G, ALIGNED, WIDE>), grid, dim3(kBlockThreads), 0, st, a);
+        if (a.mode == ES_FASTRAND)                         // with Equation 2's strided slots compiled in
+            hipLaunchKernelGGL((es_spmm_flat_kernel<G, ALIGNED, WIDE, true, 2>), grid, dim3(kBlockThreads), 0, st, a);
+        else if (a.mode == ES_BUCKET)
+            hipLaunchKernelGGL((es_spmm_flat_kernel<G, ALIGNED, WIDE, false, 2>), grid, dim3(kBlockThreads), 0, st, a);
+        else
+            hipLaunchKernelGGL((es_spmm_flat_kernel<G, ALIGNED, WIDE, false, 1>), grid, dim3(kBlockThreads), 0, st, a);
         return hipGetLastError();
     }
     a.cuts = cuts;
@@ -312,7 +317,9 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
     // The flattened kernel applies to 128-bit accesses; FastRand in the
     // partitioned product needs the row kernel's per-row walk over all W slots.
     const bool flat_applies = !backward && s.vec == 4 && !(p->partition && mode == ES_FASTRAND);
-    const bool flat_allowed = flat_applies && ov.kernel != 1;
+    // chosen by rule only on 16-byte-aligned rows: 32-column slices of rows that do
+    // not tile 128-byte lines fetch every line twice (F = 41: 0.7x)
+    const bool flat_allowed = flat_applies && ov.kernel != 1 && s.aligned;
 
     // Column slicing: fewer lanes across the feature columns, the rows swept once
     // per slice, so that the part of X in use at a time is smaller.  A slice makes
@@ -367,9 +374,10 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
     }
     p->logR = logR;
 
-    if (p->flat) {                                         // a wave lays 256 / G rows end to end
+    if (p->flat) {                                         // a wave lays 1 or 2 rows per edge slot end to end
+        const int rps = p->partition ? kFlatPartRps : mode == ES_FULL ? 1 : 2;
         logR = 0;
-        while ((1 << logR) < 256 / s.G) ++logR;
+        while ((1 << logR) < rps * 64 / s.G) ++logR;
         p->logR = logR;
     }
     const int64_t rows_per_block = (int64_t)kWavesPerBlock << logR;

@@ -73,6 +73,7 @@ template <bool ALIGNED> struct Pack<4, ALIGNED> {
         v.x = fmaf(a, x.v.x, v.x); v.y = fmaf(a, x.v.y, v.y);
         v.z = fmaf(a, x.v.z, v.z); v.w = fmaf(a, x.v.w, v.w);
     }
+    __device__ __forceinline__ void mul(float a, const Pack& x) { v.x = a * x.v.x; v.y = a * x.v.y; v.z = a * x.v.z; v.w = a * x.v.w; }
     __device__ __forceinline__ void scale(float f) { v.x *= f; v.y *= f; v.z *= f; v.w *= f; }
     __device__ __forceinline__ void add(const Pack& o) { v.x += o.v.x; v.y += o.v.y; v.z += o.v.z; v.w += o.v.w; }
     __device__ __forceinline__ void add_xor(int mask)

@@ -17,7 +17,7 @@ def _check(info, N, F, backward):
     R, E = info["rows_per_wave"], info["edge_slots"]
     assert V in (1, 4) and CH in (1, 2, 4) and G in (4, 8, 16, 32, 64)
     if info["flattened"]:
-        assert R * G == 256 and E * G == 64               # a wave lays 4E rows end to end for its E slots
+        assert R * G in (64, 128) and E * G == 64         # a wave lays E or 2E rows end to end for its E slots
     else:
         assert R * G * E == 64 and E >= 1                 # a wave is R rows x E slots x G lanes
     assert info["loads_in_flight"] * CH == 8
@@ -141,8 +141,9 @@ def test_flattened_kernel_choice():
     the partitioned product once a 64-column share outgrows an L2, and tables of
     0.3 GB and more with F >= 128; the row kernel everywhere else."""
     big = es.es_spmm_launch_info(2_450_000, 119_569_270, 128, 32, "fastrand")
-    assert big["flattened"] == 1 and big["lanes_per_row"] == 8 and big["grid_y"] == 4 and big["rows_per_wave"] == 32
-    assert es.es_spmm_launch_info(2_450_000, 119_569_270, 128, 0, "full")["flattened"] == 1
+    assert big["flattened"] == 1 and big["lanes_per_row"] == 8 and big["grid_y"] == 4 and big["rows_per_wave"] == 16
+    exact = es.es_spmm_launch_info(2_450_000, 119_569_270, 128, 0, "full")
+    assert exact["flattened"] == 1 and exact["rows_per_wave"] == 8            # one row per slot: evens the waves out
     row = es.es_spmm_launch_info(2_450_000, 119_569_270, 128, 32, "fastrand", opts=dict(kernel=1))
     assert row["flattened"] == 0 and row["lanes_per_row"] == 16
     dense = es.es_spmm_launch_info(233_000, 113_134_823, 64, 0, "full")
@@ -153,6 +154,9 @@ def test_flattened_kernel_choice():
     assert es.es_spmm_launch_info(233_000, 113_134_823, 256, 64, "fastrand")["flattened"] == 0   # 0.24 GB table
     assert es.es_spmm_launch_info(170_000, 2_370_240, 128, 16, "bucket")["flattened"] == 0
     assert es.es_spmm_launch_info(2_450_000, 119_569_270, 128, 32, "fastrand", backward=True)["flattened"] == 0
+    # rows that do not tile 128-byte lines (F = 41, stride 41) keep the row kernel on whole rows
+    odd = es.es_spmm_launch_info(233_000, 113_134_823, 41, 0, "full", aligned16=False)
+    assert odd["flattened"] == 0 and odd["column_ranges"] == 8 and odd["lanes_per_row"] == 16
 
 
 def test_flattened_kernel_option():
@@ -160,7 +164,7 @@ def test_flattened_kernel_option():
         info = es.es_spmm_launch_info(100_000, 1_000_000, F, 16, "fastrand", aligned16=(F % 4 == 0),
                                       opts=dict(kernel=2, lanes_per_row=-1))
         assert info["flattened"] == 1 and info["lanes_per_row"] == G and info["chunks_per_lane"] == 1
-        assert info["rows_per_wave"] == 256 // G and info["edge_slots"] == 64 // G
+        assert info["rows_per_wave"] == 128 // G and info["edge_slots"] == 64 // G   # sampled: two rows per slot
         assert info["grid_y"] == -(-F // (4 * G))
         _check(info, 100_000, F, False)
     assert es.es_spmm_launch_info(1000, 5000, 3, 2, "bucket", opts=dict(kernel=2))["flattened"] == 0    # F < 4
