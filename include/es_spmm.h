@@ -73,7 +73,9 @@ typedef enum {
  *             `seed`, reduced mod n (a per-row rotation; the picks stay distinct)
  *     Y[r, c] = sum over the k slots of vals[p] * X[colidx[p], c],  c in [0, F)
  * Y is overwritten (rows with n == 0 become zeros).  Accumulation is fp32; the
- * summation order is unspecified.
+ * summation order is unspecified.  X is meant to hold finite values: a kernel
+ * may add zero times a row of X that the output row gathers anyway, so an
+ * output element whose exact value is +-Inf may come out as NaN.
  *
  *   rowptr  [N+1] int32          colidx [nnz] int32
  *   vals    [nnz] fp32, or NULL = every stored entry is 1 (unweighted graph)
