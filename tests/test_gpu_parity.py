@@ -63,7 +63,8 @@ def test_small_graph_all_modes(es, F, ldx):
                                          what=f"{mode} F={F} W={W} seed={seed} rpw={rpw}", opts=opts)
     # the flattened kernel (needs 128-bit accesses: F >= 4), whole and sliced, with and without long rows
     if F >= 4:
-        for opts in (dict(kernel=2), dict(kernel=2, lanes_per_row=4), dict(kernel=2, long_row_threshold=5)):
+        for opts in (dict(kernel=2), dict(kernel=2, lanes_per_row=4), dict(kernel=2, lanes_per_row=8),
+                     dict(kernel=2, long_row_threshold=5)):
             info = es.es_spmm_launch_info(n, colidx.size, F, 3, "fastrand", ldx=ldx, ldy=ldx, opts=opts,
                                           aligned16=(F % 4 == 0 and ldx % 4 == 0))
             assert info["flattened"] == 1
