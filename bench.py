@@ -395,9 +395,11 @@ def main() -> int:
                     help="config 5 only: which SpMM stage of the 2-layer GCN forward to time")
     ap.add_argument("--main-only", action="store_true",
                     help="only the timed sweep of --config (what the rocprofv3 summaries profile)")
-    ap.add_argument("--only", choices=("sweep", "backward", "aux"), default="sweep",
+    ap.add_argument("--only", choices=("sweep", "backward", "aux", "calls"), default="sweep",
                     help="backward / aux: run only the transposed-product or the sampled-graph export "
-                         "kernels of --config a few times (for rocprofv3) and print their timings")
+                         "kernels of --config a few times (for rocprofv3) and print their timings; "
+                         "calls: only the per-call timing table of --config (also for builds of the "
+                         "library loaded through ES_SPMM_LIBRARY)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", action="store_true",
                     help="first run kernels of known traffic (1 GiB copies, a strided-read probe) that "
@@ -438,8 +440,12 @@ def main() -> int:
         traffic_key = f"config{args.config}"
 
     if args.only != "sweep":
-        rows = (backward_table(dw, dev, [c for c in calls if c[0] != "full"][:6]) if args.only == "backward"
-                else aux_table(dw, dev, calls))
+        if args.only == "calls":
+            rows = per_call_table(dw, calls, 20, None, 0)
+            log_rows(f"cfg{args.config}", rows)
+        else:
+            rows = (backward_table(dw, dev, [c for c in calls if c[0] != "full"][:6]) if args.only == "backward"
+                    else aux_table(dw, dev, calls))
         print(json.dumps({"workload": workload_text, "only": args.only, "result": rows}), flush=True)
         return 0
 

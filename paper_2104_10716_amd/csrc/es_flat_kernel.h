@@ -28,6 +28,7 @@ namespace {
 // product).
 // ---------------------------------------------------------------------------
 constexpr int kFlatTile = 256;                        // staged entries per tile
+constexpr int kFlatLongRow = 8192;                    // kept entries above which a row goes to the long-row part
 constexpr int kFlatPartRps = 2;                       // rows per edge slot in the column-partitioned product
 constexpr int kFlatAccFloats = 512;                   // NR rows x 4G columns at most
 constexpr int kFlatMaxRows = 32;                      // NR at most
@@ -265,7 +266,15 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
 #pragma unroll
             for (int u = 0; u < U; ++u) ed[u] = s.tile[(b0 + u) * E + e];
 #pragma unroll
-            for (int u = 0; u < U; ++u) x[u].load(K::row(a.X, ed[u].x, a.ldx) + cols.off[0]);
+            for (int u = 0; u < U; ++u) {
+#if defined(ES_PROBE_NO_GATHER)        // measurement builds only (wrong results): the kernel without stage 2's loads
+                x[u].v = make_float4(__uint_as_float(ed[u].x), 1.f, 2.f, 3.f);
+#elif defined(ES_PROBE_NEAR_GATHER)    // measurement builds only: every gather inside the first 64 KB of X
+                x[u].load(K::row(a.X, ed[u].x & 0xFFFu, a.ldx) + cols.off[0]);
+#else
+                x[u].load(K::row(a.X, ed[u].x, a.ldx) + cols.off[0]);
+#endif
+            }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const float v = __uint_as_float(ed[u].y);

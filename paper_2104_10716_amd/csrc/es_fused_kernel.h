@@ -133,6 +133,7 @@ __device__ __forceinline__ void long_block(const Args& a, uint32_t bx, uint32_t 
         }
         mine += nseg[i];
     }
+    if (__syncthreads_or(mine) == 0) return;     // no long row among these 1024: the common case
     int incl = mine;                             // inclusive scan inside the wave
 #pragma unroll
     for (int d = 1; d < kWaveSize; d <<= 1) {

@@ -394,6 +394,10 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
     // the long-row part costs a second small launch and a scan of the row
     // pointers; below one tile per row that is more than the tail it removes
     if (mode != ES_FULL && p->long_k < kTileSlots) p->long_k = kTileSlots;
+    // the flattened kernel walks a long row tile by tile on one wave at no extra
+    // cost per entry, so only rows that would make a tail (tens of tiles) are split
+    // (co-purchase graph, exact product: 8192 measured 6 % faster than 2048)
+    if (p->flat && p->long_k < kFlatLongRow) p->long_k = kFlatLongRow;
     if (ov.long_k > 0) p->long_k = ov.long_k;
     const bool may_be_long = mode == ES_FULL || W > p->long_k;
     p->long_blocks = may_be_long ? ((N + kLongScanRows - 1) / kLongScanRows) * kLongSplit : 0;
