@@ -320,6 +320,49 @@ def test_long_rows_span_several_tiles(es):
                 check_edges(d, W, "bucket", seed, rpw)
 
 
+@pytest.mark.parametrize("F,lanes", [(16, 0), (32, 0), (64, 0), (64, 8), (128, 0), (128, 8), (256, 0), (41, 0)])
+def test_flattened_kernel_rows_at_tile_boundaries(es, F, lanes):
+    """The flattened kernel on row lengths around everything it counts in: the
+    edge slots of a step (1..16), a batch (64), a tile (256) and several tiles,
+    empty rows in runs, in an order that puts row starts and ends on and next to
+    tile boundaries; every mode, whole rows and column-range pieces."""
+    from gpu_util import DeviceCSR, check_against_oracle
+    n = 1200
+    rng = np.random.default_rng(900 + F + lanes)
+    menu = [0, 0, 0, 1, 2, 3, 4, 7, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 191, 192, 193,
+            255, 256, 257, 300, 511, 512, 513, 767, 768, 769, 1000, 1100]
+    for variant in range(3):
+        lengths = list(rng.permutation(menu * 2))
+        if variant == 1:                      # exact fills: runs that end on a tile boundary
+            lengths = [256, 0, 0, 128, 128, 64, 64, 64, 64, 0, 512, 8, 248, 16, 240, 1, 255] * 3
+        if variant == 2:                      # nothing but empty rows, then one entry at the very end
+            lengths = [0] * 150 + [1]
+        cols = [np.sort(rng.choice(n, size=int(L), replace=False)) for L in lengths]
+        rowptr = np.zeros(n + 1, dtype=np.int32)
+        rowptr[1:len(lengths) + 1] = np.cumsum([len(c) for c in cols])
+        rowptr[len(lengths) + 1:] = rowptr[len(lengths)]
+        colidx = np.concatenate(cols).astype(np.int32)
+        vals = rng.standard_normal(colidx.size).astype(np.float32)
+        X = rng.uniform(-1, 1, (n, F)).astype(np.float32)
+        d = DeviceCSR(rowptr, colidx, vals, X).with_workspace()
+        base = dict(kernel=2, workspace=d.default_ws)
+        if lanes:
+            base["lanes_per_row"] = lanes
+        _say(f"tile boundaries F={F} lanes={lanes} variant {variant}")
+        for extra in (dict(), dict(long_row_threshold=700), dict(column_partition=1)):
+            opts = dict(base, **extra)
+            info = es.es_spmm_launch_info(n, colidx.size, F, 0, "full", aligned16=(F % 4 == 0),
+                                          opts={k: v for k, v in opts.items() if k != "workspace"})
+            assert info["flattened"] == 1, info
+            check_against_oracle(d, 0, "full", what=f"full F={F} {extra} variant {variant}", opts=opts)
+            for mode in ("bucket", "fastrand"):
+                for W in (1, 7, 8, 64, 255, 256, 257, 1024):
+                    for seed in (0, 99):
+                        check_against_oracle(d, W, mode, seed, norm="mean",
+                                             what=f"{mode} W={W} seed={seed} F={F} {extra} variant {variant}",
+                                             opts=opts)
+
+
 def test_degenerate_inputs(es):
     import torch
     from gpu_util import DeviceCSR, check_against_oracle
