@@ -51,27 +51,21 @@ struct FlatJob {
     bool accumulate;   // add to Y instead of overwriting it (phases after the first)
 };
 
-// Lanes whose bit BIT is clear get a + a', the others b + b', where a', b' are
-// the values of the lane that differs in that bit alone.  Bits 4 and 5 are the
-// row and half-wave swaps of gfx950 (odd rows of the first operand trade places
-// with even rows of the second; the upper half of the first with the lower half
-// of the second), bit 3 a rotation by 8 inside a row of 16; no LDS traffic.
+// Lanes whose bit BIT (4 or 5) is clear get a + a', the others b + b', where a',
+// b' are the values of the lane that differs in that bit alone: the row and
+// half-wave swaps of gfx950 (odd rows of 16 lanes of the first operand trade
+// places with even rows of the second; the upper half of the first with the lower
+// half of the second), then one add.  No LDS traffic.
 template <int BIT>
-__device__ __forceinline__ float halve_add(float a, float b, int lane)
+__device__ __forceinline__ float halve_add(float a, float b)
 {
+    static_assert(BIT == 4 || BIT == 5, "swaps of rows of 16 lanes and of half waves");
     if constexpr (BIT == 5) {
         const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
         return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-    } else if constexpr (BIT == 4) {
+    } else {
         const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
         return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-    } else {
-        const bool up = (lane >> BIT) & 1;
-        const float keep = up ? b : a, give = up ? a : b;
-        if constexpr (BIT == 3)
-            return keep + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(give), 0x128, 0xf, 0xf, true));
-        else
-            return keep + __shfl_xor(give, 1 << BIT, kWaveSize);
     }
 }
 
@@ -176,13 +170,13 @@ __device__ __forceinline__ void flat_block(const Args& a, uint32_t vb, const Fla
         if constexpr (E == 1) {
             *reinterpret_cast<float4*>(dst) = acc.v;
         } else if constexpr (E == 2) {
-            const float s0 = halve_add<5>(acc.v.x, acc.v.z, lane);
-            const float s1 = halve_add<5>(acc.v.y, acc.v.w, lane);
+            const float s0 = halve_add<5>(acc.v.x, acc.v.z);
+            const float s1 = halve_add<5>(acc.v.y, acc.v.w);
             *reinterpret_cast<float2*>(dst + 2 * e) = make_float2(s0, s1);
         } else {
-            const float s0 = halve_add<4>(acc.v.x, acc.v.z, lane);    // bit 4 clear: x, set: z
-            const float s1 = halve_add<4>(acc.v.y, acc.v.w, lane);    //              y       w
-            float v = halve_add<5>(s0, s1, lane);                     // bit 5 clear: s0, set: s1
+            const float s0 = halve_add<4>(acc.v.x, acc.v.z);    // bit 4 clear: x, set: z
+            const float s1 = halve_add<4>(acc.v.y, acc.v.w);    //              y       w
+            float v = halve_add<5>(s0, s1);                     // bit 5 clear: s0, set: s1
             if constexpr (LOG_E > 2) v = all_add<3>(v);
             if constexpr (LOG_E > 3) v = all_add<2>(v);
             const int top = e >> (LOG_E - 2);                         // lane bits 4, 5
