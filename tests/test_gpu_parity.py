@@ -658,6 +658,49 @@ def test_hip_graph_capture_and_replay(es):
         check_Y(Ys.cpu().numpy(), Yref, den, f"graph replay {rep}")
 
 
+def test_hip_graph_capture_of_the_partitioned_product(es):
+    """The column-partitioned product on the library's static workspace (one
+    cuts kernel and eight phase launches, nothing allocated, nothing but kernels)
+    inside a HIP graph, on flattened pieces and on the row form: every replay
+    equals the eager result bit for bit and stays inside the oracle's bound."""
+    import torch
+    import oracle
+    from gpu_util import DeviceCSR, check_Y
+    rowptr, colidx, vals, X = _random_graph(3000, 60.0, seed=23, F=64)
+    d = DeviceCSR(rowptr, colidx, vals, X)
+    variants = [dict(column_partition=1, kernel=2, lanes_per_row=8), dict(column_partition=1, kernel=1)]
+    outs = [torch.zeros((d.N, d.F), dtype=torch.float32, device="cuda:0") for _ in variants]
+    for opts in variants:
+        info = es.es_spmm_launch_info(d.N, colidx.size, d.F, 0, "full", opts=opts)
+        assert info["column_ranges"] == 8 and info["flattened"] == (opts["kernel"] == 2)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for Y, opts in zip(outs, variants):                     # warm-up outside capture
+            es.es_spmm_static_ws(d.rowptr, d.colidx, d.vals, d.X, Y, 0, "full", 0, "none", opts)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for Y, opts in zip(outs, variants):
+            es.es_spmm_static_ws(d.rowptr, d.colidx, d.vals, d.X, Y, 0, "full", 0, "none", opts)
+    for rep in range(3):
+        for Y in outs:
+            Y.fill_(float("nan"))
+        if rep == 1:
+            d.X.mul_(2.0)                                       # new input values, same buffers
+            d.h_X = d.h_X * np.float32(2.0)
+        g.replay()
+        torch.cuda.synchronize()
+        Yref, den = oracle.spmm(rowptr, colidx, vals, d.h_X, d.F, 0, "full", 0)
+        for Y, opts in zip(outs, variants):
+            eager = torch.empty_like(Y)
+            es.es_spmm_static_ws(d.rowptr, d.colidx, d.vals, d.X, eager, 0, "full", 0, "none", opts)
+            torch.cuda.synchronize()
+            assert torch.equal(Y, eager), f"replay {rep} {opts}: differs from the eager result"
+            check_Y(Y.cpu().numpy(), Yref, den, f"graph replay {rep} {opts}")
+
+
 def test_validate_csr(es):
     """es_spmm_validate_csr reports exactly the faults planted in a host copy of
     a sound graph (and reads nothing it should not while doing so)."""

@@ -32,7 +32,9 @@ def test_static_workspace_matches_caller_workspace_on_two_calls_in_a_row():
     assert info["column_ranges"] == 8
     cases = [(big, 0, "full", 0, None), (small, 0, "full", 0, dict(column_partition=1)),
              (big, 300, "fastrand", 7, dict(column_partition=1)), (small, 9, "fastrand", 7, dict(column_partition=1)),
-             (big, 16, "bucket", 0, None), (small, 0, "full", 0, None)]
+             (big, 16, "bucket", 0, None), (small, 0, "full", 0, None),
+             (big, 0, "full", 0, dict(kernel=2, lanes_per_row=8)),          # flattened pieces of the column ranges
+             (small, 0, "full", 0, dict(kernel=2, column_partition=1))]
     for d, W, mode, seed, opts in cases:
         what = f"static workspace N={d.N} {mode} W={W} opts={opts}"
         Ys = torch.full((d.N, d.F), float("nan"), dtype=torch.float32, device=dev)
