@@ -259,7 +259,9 @@ def test_row_offsets_beyond_32_bits(es, ld):
     Y = torch.empty((n, F), dtype=torch.float32, device=dev)
     ws = torch.empty(es.es_spmm_workspace_bytes(n) // 4, dtype=torch.int32, device=dev)
     for mode, W, opts in (("full", 0, None), ("fastrand", 5, None), ("bucket", 5, dict(long_row_threshold=3)),
-                          ("full", 0, dict(column_partition=1)), ("fastrand", 5, dict(column_partition=1))):
+                          ("full", 0, dict(column_partition=1)), ("fastrand", 5, dict(column_partition=1)),
+                          ("full", 0, dict(kernel=2)), ("fastrand", 5, dict(kernel=2)), ("bucket", 5, dict(kernel=2)),
+                          ("full", 0, dict(kernel=2, column_partition=1))):        # flattened kernel, wide keys
         Y.fill_(float("nan"))
         es.es_spmm_ws(rp, ci, va, X, Y, W, mode, 3, "none", opts, ws)
         torch.cuda.synchronize()
