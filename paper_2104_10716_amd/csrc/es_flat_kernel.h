@@ -28,7 +28,7 @@ namespace {
 // product).
 // ---------------------------------------------------------------------------
 constexpr int kFlatTile = 256;                        // staged entries per tile
-constexpr int kFlatLongRow = 8192;                    // kept entries above which a row goes to the long-row part
+constexpr int kFlatLongRow = 8192;                    // kept entries above which a row goes to the long-row part (at most)
 constexpr int kFlatPartRps = 2;                       // rows per edge slot in the column-partitioned product
 constexpr int kFlatAccFloats = 512;                   // NR rows x 4G columns at most
 constexpr int kFlatMaxRows = 32;                      // NR at most

@@ -395,9 +395,16 @@ int make_plan(int64_t N, int64_t nnz, int32_t F, int32_t W, int32_t mode, bool a
     // pointers; below one tile per row that is more than the tail it removes
     if (mode != ES_FULL && p->long_k < kTileSlots) p->long_k = kTileSlots;
     // the flattened kernel walks a long row tile by tile on one wave at no extra
-    // cost per entry, so only rows that would make a tail (tens of tiles) are split
-    // (co-purchase graph, exact product: 8192 measured 6 % faster than 2048)
-    if (p->flat && p->long_k < kFlatLongRow) p->long_k = kFlatLongRow;
+    // cost per entry, so only rows that would make a tail are split: a row of k
+    // entries keeps its wave busy for about k * 16 ns, the whole launch takes about
+    // entries * 50 ps, and the tail should stay below a tenth of that (co-purchase
+    // graph, exact product: 8192 measured 6 % faster than 2048; citation graph,
+    // 2.4 M entries: 8192 would leave one 12 k row running alone for half the launch)
+    if (p->flat) {
+        const double tail_free = entries * 3.0e-4;
+        const int32_t k = tail_free >= (double)kFlatLongRow ? kFlatLongRow : (int32_t)tail_free;
+        if (p->long_k < k) p->long_k = k;
+    }
     if (ov.long_k > 0) p->long_k = ov.long_k;
     const bool may_be_long = mode == ES_FULL || W > p->long_k;
     p->long_blocks = may_be_long ? ((N + kLongScanRows - 1) / kLongScanRows) * kLongSplit : 0;
